@@ -1,0 +1,183 @@
+/*
+ * libfoldconv -- width-folded NHWC convolution for gfx950 (MI355X).
+ *
+ * C ABI.  Every tensor pointer is a DEVICE pointer owned by the caller; the
+ * library allocates no device memory, never frees anything the caller passed
+ * and never synchronises: each call enqueues its kernels on `stream`
+ * (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ * Inputs are read-only, outputs are fully overwritten.  Every function
+ * returns FOLDCONV_OK (0) or a negative status; nothing throws across the
+ * boundary.  A plan is host memory owned by the library until
+ * foldconv_plan_destroy().
+ *
+ * Notation (paper: Algorithm 1, REQUIRE; section "Width-Folding
+ * Transformation as an IR Transformation"):
+ *   x  [N][H][W][C_in]            input, NHWC, row-major
+ *   w  [KH][KW][C_in][C_out]      filter, HWIO
+ *   b  [C_out]                    bias, same dtype as x
+ *   F                             fold factor; W must be divisible by F
+ *   x' [N][H][W/F][F*C_in]        folded input      (Eq. "width_fold_def")
+ *   w' [KH][KW'][F*C_in][F*C_out] expanded filter   (Eq. "filter_construct")
+ *   y' [N][H_out][W'_out][F*C_out] folded output    (Eq. "new_conv_H")
+ *   y  [N][H_out][W_out][C_out]   reconstructed output ("Reconstruct" step)
+ * Stride 1, cross-correlation (no kernel flip), symmetric zero padding `pad`
+ * applied along an axis only when the kernel extends along it (KH > 1 for H,
+ * KW > 1 for W), so Conv1d is H = KH = 1.
+ *
+ * The paper defines and proves the rewrite for a K x 1 kernel with C_in = 1
+ * (convolution along H only).  For taps along the folded axis the expanded
+ * filter becomes block-banded over KW' = d_max - d_min + 1 folded taps,
+ *   d_min = floor(-p/F),  d_max = floor((F + KW - 2 - p)/F),
+ *   w'[kh][d-d_min][f*C_in+c][g*C_out+co] = w[kh][F*d+f-g+p][c][co]
+ * when that tap index lies in [0, KW), else 0; for KW = 1, p = 0 this is the
+ * paper's block diagonal.
+ */
+#ifndef FOLDCONV_H
+#define FOLDCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FOLDCONV_API __attribute__((visibility("default")))
+
+typedef struct foldconv_plan_s *foldconv_plan_t;
+
+typedef enum { FOLDCONV_F32 = 0, FOLDCONV_F16 = 1, FOLDCONV_BF16 = 2 } foldconv_dtype_t;
+
+enum {
+    FOLDCONV_OK = 0,
+    FOLDCONV_ERR_BADARG = -1,      /* null pointer, non-positive size, unknown dtype/flag     */
+    FOLDCONV_ERR_INDIVISIBLE = -2, /* W % F != 0 (paper: guard at the top of Algorithm 1)     */
+    FOLDCONV_ERR_UNSUPPORTED = -3, /* empty output, sizes beyond 32-bit tile indexing         */
+    FOLDCONV_ERR_WORKSPACE = -4,   /* workspace missing, too small or not 256-byte aligned    */
+    FOLDCONV_ERR_HIP = -5          /* a HIP launch failed; hipGetLastError() was consumed     */
+};
+
+enum {
+    FOLDCONV_FLAG_RELU = 1u,          /* y = max(0, conv + bias)                               */
+    FOLDCONV_FLAG_DENSE_K = 2u,       /* walk every K-step of w', structural zeros included,
+                                         instead of only the band that can be non-zero for the
+                                         output slots of a tile.  Same result for finite data. */
+    FOLDCONV_FLAG_KEEP_FOLDED = 4u,   /* write y' [N][H_out][W'_out][F*C_out], not y           */
+    FOLDCONV_FLAG_FILTER_PACKED = 8u  /* workspace already holds the packed filter written by a
+                                         previous call with the same plan and the same filter
+                                         (weights are static after training): skip re-packing  */
+};
+
+/* Everything a caller needs to size buffers and to report throughput. */
+typedef struct foldconv_shapes_s {
+    int32_t N, H, W, C_in, C_out, KH, KW, pad, F, dtype;
+    int32_t pad_h, pad_w;           /* per-axis padding actually applied                     */
+    int32_t W_fold;                 /* W / F                                                  */
+    int32_t C_fold;                 /* F * C_in                                               */
+    int32_t Co_fold;                /* F * C_out  (GEMM N)                                    */
+    int32_t d_min, d_max, KW_fold;  /* folded tap range and count                             */
+    int32_t pad_left_fold, pad_right_fold; /* zero columns the folded problem needs          */
+    int32_t H_out, W_out, W_out_fold;      /* W_out_fold = ceil(W_out / F)                    */
+    int32_t unfold_is_alias;        /* 1 when y and y' are the same bytes (W_out == F*W'_out) */
+    int32_t C_pad;                  /* channel count used by conv_padded_forward              */
+    int32_t elem_bytes;
+    int32_t conv_kernel;            /* 0 = gather MFMA, 1 = LDS-tiled MFMA, 2 = streaming MFMA
+                                       (which kernel foldconv_forward will launch)            */
+    int32_t padded_kernel;          /* same, for conv_padded_forward                          */
+    int64_t gemm_M, gemm_N, gemm_K; /* implicit GEMM of the folded problem, dense K           */
+    int64_t x_bytes, w_bytes, bias_bytes, w_exp_bytes, y_bytes, y_fold_bytes;
+    int64_t workspace_bytes;        /* for foldconv_forward / foldconv_pack_filter            */
+    int64_t padded_workspace_bytes; /* for conv_padded_forward                                */
+    double useful_flops;            /* 2*N*H_out*W_out*C_out*KH*KW*C_in                       */
+    double issued_flops_dense;      /* MFMA flops issued with FOLDCONV_FLAG_DENSE_K           */
+    double issued_flops_band;       /* MFMA flops issued by the default band walk             */
+    double issued_flops_padded;     /* MFMA flops issued by conv_padded_forward               */
+} foldconv_shapes_t;
+
+/*
+ * Build a plan: legality test and all closed forms of the folded problem.
+ * paper: Algorithm 1 (guard, shapes of X_f, W_f', b'); legality paragraph of
+ * "Compiler-Level Realization in MLIR".  Unlike Algorithm 1 an illegal fold
+ * is an error (FOLDCONV_ERR_INDIVISIBLE), not a silent fallback, and
+ * C_in != 1 is supported through c' = f*C_in + c ("Mathematical
+ * Perspective").  Host only; no GPU call is made.
+ */
+FOLDCONV_API int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
+                  int fold_factor, foldconv_dtype_t dtype, foldconv_plan_t *out);
+
+/* Copy the plan's derived shapes into *out (host memory of the caller). */
+FOLDCONV_API int foldconv_plan_query(foldconv_plan_t plan, foldconv_shapes_t *out);
+
+/* Release a plan.  NULL is ignored. */
+FOLDCONV_API void foldconv_plan_destroy(foldconv_plan_t plan);
+
+/*
+ * Structured filter expansion  w [KH][KW][C_in][C_out] -> w' (layout above),
+ * zeros written explicitly; bit-exact copy of the filter values.
+ * paper: Eq. "filter_construct"; Algorithm 1 "Define W_f' ... initialize to
+ * zero" and the copy loop.  w_exp must hold shapes.w_exp_bytes.
+ */
+FOLDCONV_API int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream);
+
+/*
+ * Input width fold  x -> x' with x'[n][h][w'][f*C_in+c] = x[n][h][F*w'+f][c].
+ * paper: Eq. "width_fold_def"; Algorithm 1 loop nest.  In contiguous NHWC the
+ * two tensors have identical linear offsets, so x_fold == x is legal and
+ * returns at once without launching anything (the paper's listing folds with
+ * a reshape); otherwise a vectorised copy of shapes.x_bytes is enqueued.
+ * The buffers must not partially overlap.
+ */
+FOLDCONV_API int foldconv_fold_input(foldconv_plan_t plan, const void *x, void *x_fold, void *stream);
+
+/*
+ * Reconstruct  y'[n][h][w'][g*C_out+co] -> y[n][h][F*w'+g][co], dropping
+ * columns F*w'+g >= W_out.  paper: "Let w = F w' + f" in the correctness
+ * section; Reconstruct step of the IR formulation.  y == y_fold is legal only
+ * when shapes.unfold_is_alias (then nothing is launched).
+ */
+FOLDCONV_API int foldconv_unfold_output(foldconv_plan_t plan, const void *y_fold, void *y, void *stream);
+
+/*
+ * Re-order w' into the operand order of the MFMA kernels (8 consecutive K
+ * values of one output column per 16 bytes) inside `workspace`.  Optional:
+ * foldconv_forward does this itself unless FOLDCONV_FLAG_FILTER_PACKED is
+ * given.  Needs shapes.workspace_bytes (0 when the plan runs the gather
+ * kernel, which reads w' directly; then this is a no-op).
+ */
+FOLDCONV_API int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Folded convolution + bias (+ReLU) + reconstruct:
+ *   y'[n][h][w'][g*C_out+co] = b[co] + sum_{kh,d,c'} x'[n][h+kh-pad_h][w'+d][c'] * w'[kh][d-d_min][c'][g*C_out+co]
+ * with out-of-range x' read as zero, fp32 accumulation, one rounding to the
+ * plan dtype, written straight into y (reconstructed layout) unless
+ * FOLDCONV_FLAG_KEEP_FOLDED.  paper: Eq. "new_conv_H"; Eq. "bias_construct"
+ * (the replicated bias is read as b[n mod C_out]); Reconstruct step.
+ * bias may be NULL.  workspace: shapes.workspace_bytes, 256-byte aligned,
+ * may be NULL when that is 0.
+ */
+FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
+                     const void *bias, void *y, void *workspace, size_t workspace_bytes,
+                     unsigned flags, void *stream);
+
+/*
+ * Reference path: zero-pad C_in up to shapes.C_pad in the input and the
+ * filter, then run the same convolution kernels unfolded (F = 1).
+ * paper: the zero-padding alternative in the Introduction and in "Difference
+ * from Channel Zero-Padding".  x and w are the ORIGINAL tensors; the padded
+ * copies live in workspace (shapes.padded_workspace_bytes).  With
+ * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again.
+ * FOLDCONV_FLAG_KEEP_FOLDED and FOLDCONV_FLAG_DENSE_K are ignored.
+ */
+FOLDCONV_API int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias,
+                        void *y, void *workspace, size_t workspace_bytes, unsigned flags,
+                        void *stream);
+
+/* Static text for a status code. */
+FOLDCONV_API const char *foldconv_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOLDCONV_H */

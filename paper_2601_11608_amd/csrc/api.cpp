@@ -1,0 +1,112 @@
+// The extern "C" entry points that enqueue GPU work: argument checks,
+// workspace carving and the choice between the convolution kernels.
+#include <stdint.h>
+
+#include "geom.h"
+#include "launch.h"
+
+static bool plan_ok(foldconv_plan_t p) { return p && p->magic == FOLDCONV_MAGIC; }
+static bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+static int hip_status(int e) { return e == 0 ? FOLDCONV_OK : FOLDCONV_ERR_HIP; }
+
+static const unsigned kAllFlags =
+    FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED;
+
+extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
+    if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
+    return hip_status(fc_launch_expand(plan, w, w_exp, stream));
+}
+
+extern "C" int foldconv_fold_input(foldconv_plan_t plan, const void *x, void *x_fold, void *stream) {
+    if (!plan_ok(plan) || !x || !x_fold) return FOLDCONV_ERR_BADARG;
+    if (x == x_fold) return FOLDCONV_OK;  // identical linear offsets: the fold is the identity on bytes
+    const uintptr_t a = (uintptr_t)x, b = (uintptr_t)x_fold, n = (uintptr_t)plan->s.x_bytes;
+    if (a < b + n && b < a + n) return FOLDCONV_ERR_BADARG;  // partial overlap
+    return hip_status(fc_launch_copy(x, x_fold, (size_t)plan->s.x_bytes, stream));
+}
+
+extern "C" int foldconv_unfold_output(foldconv_plan_t plan, const void *y_fold, void *y, void *stream) {
+    if (!plan_ok(plan) || !y_fold || !y) return FOLDCONV_ERR_BADARG;
+    if (y == y_fold) return plan->s.unfold_is_alias ? FOLDCONV_OK : FOLDCONV_ERR_BADARG;
+    const uintptr_t a = (uintptr_t)y_fold, b = (uintptr_t)y;
+    if (a < b + (uintptr_t)plan->s.y_bytes && b < a + (uintptr_t)plan->s.y_fold_bytes) return FOLDCONV_ERR_BADARG;
+    if (plan->s.unfold_is_alias) return hip_status(fc_launch_copy(y_fold, y, (size_t)plan->s.y_bytes, stream));
+    return hip_status(fc_launch_unfold(plan, y_fold, y, stream));
+}
+
+static int check_ws(const void *ws, size_t have, long long need) {
+    if (need <= 0) return FOLDCONV_OK;
+    if (!ws || have < (size_t)need || !aligned(ws, 256)) return FOLDCONV_ERR_WORKSPACE;
+    return FOLDCONV_OK;
+}
+
+extern "C" int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
+    if (!plan_ok(plan) || !w_exp) return FOLDCONV_ERR_BADARG;
+    if (plan->s.conv_kernel == FC_KERNEL_GATHER) return FOLDCONV_OK;
+    int st = check_ws(workspace, workspace_bytes, plan->s.workspace_bytes);
+    if (st) return st;
+    if (!aligned(w_exp, 2)) return FOLDCONV_ERR_BADARG;
+    return hip_status(fc_launch_pack(plan->fold, plan->s.elem_bytes, w_exp, workspace, stream));
+}
+
+extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, const void *bias,
+                                void *y, void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!plan_ok(plan) || !x_fold || !w_exp || !y) return FOLDCONV_ERR_BADARG;
+    if (flags & ~kAllFlags) return FOLDCONV_ERR_BADARG;
+    const foldconv_shapes_t &s = plan->s;
+    const size_t eb = (size_t)s.elem_bytes;
+    if (!aligned(x_fold, eb) || !aligned(w_exp, eb) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
+        return FOLDCONV_ERR_BADARG;
+    ConvGeom g = plan->fold;
+    g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
+    g.band = (flags & FOLDCONV_FLAG_DENSE_K) ? 0 : 1;
+    g.has_bias = bias ? 1 : 0;
+    g.out_row = (flags & FOLDCONV_FLAG_KEEP_FOLDED) ? g.Wf_out * g.NCo : s.W_out * s.C_out;
+
+    int kernel = s.conv_kernel;
+    if (kernel != FC_KERNEL_GATHER) {
+        int st = check_ws(workspace, workspace_bytes, s.workspace_bytes);
+        if (st) return st;
+        // The vector kernels read 16-byte chunks; unaligned tensors are an error
+        // rather than a silent change of kernel.
+        if (!aligned(x_fold, 16) || !aligned(y, 16)) return FOLDCONV_ERR_BADARG;
+        if (!(flags & FOLDCONV_FLAG_FILTER_PACKED)) {
+            int e = fc_launch_pack(plan->fold, s.elem_bytes, w_exp, workspace, stream);
+            if (e) return FOLDCONV_ERR_HIP;
+        }
+    }
+    return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, w_exp, workspace, bias, y, stream));
+}
+
+extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias, void *y,
+                                   void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
+    if (!plan_ok(plan) || !x || !w || !y) return FOLDCONV_ERR_BADARG;
+    if (flags & ~kAllFlags) return FOLDCONV_ERR_BADARG;
+    const foldconv_shapes_t &s = plan->s;
+    const size_t eb = (size_t)s.elem_bytes;
+    if (!aligned(x, eb) || !aligned(w, eb) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
+        return FOLDCONV_ERR_BADARG;
+    int st = check_ws(workspace, workspace_bytes, s.padded_workspace_bytes);
+    if (st) return st;
+    char *ws = (char *)workspace;
+    void *x_pad = ws + plan->ws_xpad, *w_pad = ws + plan->ws_wpad, *w_pack = ws + plan->ws_wpack;
+    const int kernel = s.padded_kernel;
+    if (kernel != FC_KERNEL_GATHER && !aligned(y, 16)) return FOLDCONV_ERR_BADARG;
+
+    int e = fc_launch_pad_input(plan, x, x_pad, stream);
+    if (e) return FOLDCONV_ERR_HIP;
+    if (!(flags & FOLDCONV_FLAG_FILTER_PACKED)) {
+        e = fc_launch_pad_filter(plan, w, w_pad, stream);
+        if (e) return FOLDCONV_ERR_HIP;
+        if (kernel != FC_KERNEL_GATHER) {
+            e = fc_launch_pack(plan->padc, s.elem_bytes, w_pad, w_pack, stream);
+            if (e) return FOLDCONV_ERR_HIP;
+        }
+    }
+    ConvGeom g = plan->padc;
+    g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
+    g.band = 1;
+    g.has_bias = bias ? 1 : 0;
+    return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_pad, w_pad, w_pack, bias, y, stream));
+}

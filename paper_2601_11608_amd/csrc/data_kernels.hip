@@ -1,0 +1,255 @@
+// Data-movement kernels of libfoldconv for gfx950: filter expansion, the
+// fold copy, reconstruct (row-cropping copy), channel zero-padding for the
+// reference path, and the re-ordering of the expanded filter into MFMA
+// operand order.  All are pure moves of element bits (no arithmetic), so
+// they are templated on the element's storage width only.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "launch.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte lane access
+
+inline unsigned blocks_for(long long work, int per_block, long long cap) {
+    long long b = (work + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+// ---------------------------------------------------------------------------
+// Structured filter expansion (paper: Eq. "filter_construct", Algorithm 1).
+// One thread per element of w'; every element is written, zeros included, so
+// the destination needs no prior clearing.  Gather form of the band:
+//   w'[kh][dd][f*C+c][g*Co+co] = w[kh][F*(dd+d_min)+f-g+p][c][co]  if that tap
+//   index is inside [0, KW), else 0.
+// ---------------------------------------------------------------------------
+template <typename U>
+__global__ void __launch_bounds__(kThreads)
+expand_filter_kernel(const U *__restrict__ w, U *__restrict__ we, int KH, int KW, int C, int Co, int F,
+                     int KWf, int d_min, int p, long long total) {
+    const long long stride = (long long)gridDim.x * kThreads;
+    const int FC = F * C, FCo = F * Co;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        int nn = (int)(i % FCo);
+        long long r = i / FCo;
+        int cf = (int)(r % FC);
+        r /= FC;
+        int dd = (int)(r % KWf);
+        int kh = (int)(r / KWf);
+        int f = cf / C, c = cf - f * C;
+        int g = nn / Co, co = nn - g * Co;
+        int kw = F * (dd + d_min) + f - g + p;
+        U v = 0;
+        if (kw >= 0 && kw < KW) v = w[(((long long)kh * KW + kw) * C + c) * Co + co];
+        we[i] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Straight copy, 16 bytes per lane per access, four independent accesses in
+// flight per lane.  The width fold of a contiguous NHWC tensor is this copy
+// (paper: Eq. "width_fold_def"; equal linear offsets before and after).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads)
+copy16_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, long long n16) {
+    const long long stride = (long long)gridDim.x * kThreads;
+    long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        u32x4 a = __builtin_nontemporal_load(src + i);
+        u32x4 b = __builtin_nontemporal_load(src + i + stride);
+        u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride);
+        u32x4 d = __builtin_nontemporal_load(src + i + 3 * stride);
+        __builtin_nontemporal_store(a, dst + i);
+        __builtin_nontemporal_store(b, dst + i + stride);
+        __builtin_nontemporal_store(c, dst + i + 2 * stride);
+        __builtin_nontemporal_store(d, dst + i + 3 * stride);
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ void __launch_bounds__(kThreads)
+copy1_kernel(const unsigned char *__restrict__ src, unsigned char *__restrict__ dst, long long n) {
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------
+// Reconstruct with a ragged tail (paper: Reconstruct step): destination rows
+// hold the first `dst_row` units of source rows of `src_row` units.
+// ---------------------------------------------------------------------------
+template <typename V>
+__global__ void __launch_bounds__(kThreads)
+crop_rows_kernel(const V *__restrict__ src, V *__restrict__ dst, long long rows, int src_row, int dst_row) {
+    const long long total = rows * dst_row;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        long long r = i / dst_row;
+        int c = (int)(i - r * dst_row);
+        dst[i] = src[r * src_row + c];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Channel zero-padding of the input for the reference path: one 16-byte
+// chunk of x_pad per thread (C_pad is a multiple of 8, so a chunk never
+// straddles pixels).  paper: the zero-padding alternative.
+// ---------------------------------------------------------------------------
+template <typename U>
+__global__ void __launch_bounds__(kThreads)
+pad_input_kernel(const U *__restrict__ x, U *__restrict__ xp, long long pixels, int C, int C_pad) {
+    constexpr int EPC = 16 / sizeof(U);
+    const int cpp = C_pad / EPC;  // chunks per pixel
+    const long long total = pixels * cpp;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        long long pix = i / cpp;
+        int c0 = (int)(i - pix * cpp) * EPC;
+        U v[EPC];
+#pragma unroll
+        for (int j = 0; j < EPC; ++j) {
+            int c = c0 + j;
+            v[j] = c < C ? x[pix * C + c] : (U)0;
+        }
+        u32x4 out;
+        __builtin_memcpy(&out, v, 16);
+        reinterpret_cast<u32x4 *>(xp)[i] = out;
+    }
+}
+
+template <typename U>
+__global__ void __launch_bounds__(kThreads)
+pad_filter_kernel(const U *__restrict__ w, U *__restrict__ wp, int taps, int C, int C_pad, int Co) {
+    const long long total = (long long)taps * C_pad * Co;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        int co = (int)(i % Co);
+        long long r = i / Co;
+        int c = (int)(r % C_pad);
+        long long t = r / C_pad;
+        wp[i] = c < C ? w[(t * C + c) * Co + co] : (U)0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Expanded filter -> MFMA operand order for 16-bit types:
+//   pack[kh][q][n][j] = w'[kh*kwin + 8*q + j][n],  j = 0..7  (16 bytes)
+// so that one lane's eight consecutive K values of one output column are a
+// single 16-byte load.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads)
+pack_filter_kernel(const uint16_t *__restrict__ we, u32x4 *__restrict__ pack, int KH, int kwin, int NCo) {
+    const int q_per_kh = kwin / 8;
+    const long long total = (long long)KH * q_per_kh * NCo;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        int n = (int)(i % NCo);
+        long long r = i / NCo;  // kh*q_per_kh + q  ==  first filter row / 8
+        const uint16_t *srcp = we + (r * 8) * NCo + n;
+        uint16_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = srcp[(long long)j * NCo];
+        u32x4 out;
+        __builtin_memcpy(&out, v, 16);
+        pack[i] = out;
+    }
+}
+
+inline int last_error() { return (int)hipGetLastError(); }
+
+}  // namespace
+
+int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    const long long total = s.gemm_K * s.gemm_N;
+    const unsigned grid = blocks_for(total, kThreads, 1 << 16);
+    hipStream_t st = (hipStream_t)stream;
+    if (s.elem_bytes == 2)
+        expand_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (uint16_t *)w_exp, s.KH, s.KW,
+                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total);
+    else
+        expand_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (uint32_t *)w_exp, s.KH, s.KW,
+                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total);
+    return last_error();
+}
+
+int fc_launch_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (bytes == 0) return 0;
+    if (((uintptr_t)src | (uintptr_t)dst) % 16 == 0) {
+        const long long n16 = (long long)(bytes / 16);
+        if (n16 > 0) {
+            // 4 x 16 B per lane per trip; enough blocks to cover all 256 CUs several times over.
+            const unsigned grid = blocks_for(n16, kThreads * 4, 256 * 16);
+            copy16_kernel<<<grid, kThreads, 0, st>>>((const u32x4 *)src, (u32x4 *)dst, n16);
+        }
+        const size_t tail = bytes % 16;
+        if (tail)
+            copy1_kernel<<<1, kThreads, 0, st>>>((const unsigned char *)src + (bytes - tail),
+                                                 (unsigned char *)dst + (bytes - tail), (long long)tail);
+    } else {
+        copy1_kernel<<<blocks_for((long long)bytes, kThreads, 1 << 16), kThreads, 0, st>>>(
+            (const unsigned char *)src, (unsigned char *)dst, (long long)bytes);
+    }
+    return last_error();
+}
+
+int fc_launch_unfold(const foldconv_plan_s *p, const void *y_fold, void *y, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    const long long rows = (long long)s.N * s.H_out;
+    const long long src_row_b = (long long)s.W_out_fold * s.Co_fold * s.elem_bytes;
+    const long long dst_row_b = (long long)s.W_out * s.C_out * s.elem_bytes;
+    if (src_row_b % 16 == 0 && dst_row_b % 16 == 0 && ((uintptr_t)y_fold | (uintptr_t)y) % 16 == 0) {
+        const unsigned grid = blocks_for(rows * (dst_row_b / 16), kThreads, 256 * 32);
+        crop_rows_kernel<u32x4><<<grid, kThreads, 0, st>>>((const u32x4 *)y_fold, (u32x4 *)y, rows,
+                                                           (int)(src_row_b / 16), (int)(dst_row_b / 16));
+    } else if (s.elem_bytes == 2) {
+        const unsigned grid = blocks_for(rows * (dst_row_b / 2), kThreads, 256 * 32);
+        crop_rows_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)y_fold, (uint16_t *)y, rows,
+                                                              (int)(src_row_b / 2), (int)(dst_row_b / 2));
+    } else {
+        const unsigned grid = blocks_for(rows * (dst_row_b / 4), kThreads, 256 * 32);
+        crop_rows_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)y_fold, (uint32_t *)y, rows,
+                                                              (int)(src_row_b / 4), (int)(dst_row_b / 4));
+    }
+    return last_error();
+}
+
+int fc_launch_pad_input(const foldconv_plan_s *p, const void *x, void *x_pad, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    const long long pixels = (long long)s.N * s.H * s.W;
+    const long long chunks = pixels * s.C_pad * s.elem_bytes / 16;
+    const unsigned grid = blocks_for(chunks, kThreads, 256 * 32);
+    if (s.elem_bytes == 2)
+        pad_input_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)x, (uint16_t *)x_pad, pixels, s.C_in, s.C_pad);
+    else
+        pad_input_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)x, (uint32_t *)x_pad, pixels, s.C_in, s.C_pad);
+    return last_error();
+}
+
+int fc_launch_pad_filter(const foldconv_plan_s *p, const void *w, void *w_pad, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    const int taps = s.KH * s.KW;
+    const long long total = (long long)taps * s.C_pad * s.C_out;
+    const unsigned grid = blocks_for(total, kThreads, 1 << 16);
+    if (s.elem_bytes == 2)
+        pad_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (uint16_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out);
+    else
+        pad_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (uint32_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out);
+    return last_error();
+}
+
+int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream) {
+    if (elem_bytes != 2 || g.kwin % 8 != 0) return (int)hipErrorInvalidValue;
+    hipStream_t st = (hipStream_t)stream;
+    const long long total = (long long)g.KH * (g.kwin / 8) * g.NCo;
+    const unsigned grid = blocks_for(total, kThreads, 1 << 16);
+    pack_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    return last_error();
+}

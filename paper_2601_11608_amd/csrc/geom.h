@@ -1,0 +1,74 @@
+// Geometry of one (possibly folded) convolution as the kernels see it, plus
+// the plan object behind the C ABI.  Host and device share this header.
+//
+// The folded problem is an implicit GEMM  y'^T[n][m] = sum_k w'[k][n] * A[m][k]
+// with m = (image, output row, folded output column), n = g*C_out + co and
+// k = (kh, e), where e is the "extended channel" coordinate of a tap relative
+// to the folded pixel: e = d*F*C_in + c'.  Because x' is contiguous NHWC, the
+// element for (m, kh, e) sits at   row(image, h+kh-pad_h) + w'*F*C_in + e,
+// i.e. one contiguous window of the input row per (m, kh), and the matching
+// filter row is  kh*KW'*F*C_in + (e - e_min).  Output slot g only has
+// non-zero filter rows for e in [(g-p)*C_in, (g+KW-p)*C_in): the block band
+// of the expanded filter (paper: Eq. "filter_construct" generalised to taps
+// along the folded axis).
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/foldconv.h"
+
+#if defined(__HIPCC__)
+#define FC_HD __host__ __device__ inline
+#else
+#define FC_HD inline
+#endif
+
+struct ConvGeom {
+    int N, H, Hout;
+    int Wf;      // folded input width in pixels
+    int Wf_out;  // folded output width in pixels
+    int FC;      // channels per folded input pixel (F*C_in)
+    int NCo;     // GEMM N: channels per folded output pixel (F*C_out)
+    int Co;      // bias period (C_out)
+    int C;       // original input channels (band arithmetic)
+    int F, KH, KW, pad_h, pad_w;
+    int e_min, e_max;  // dense window of extended channels, [e_min, e_max)
+    int kwin;          // e_max - e_min = KW'*FC = filter rows per kh
+    int in_row;        // elements per input row  (Wf*FC)
+    int out_row;       // elements per stored output row (W_out*Co, or Wf_out*NCo when kept folded)
+    int relu, band, has_bias;
+    long long M;       // N*Hout*Wf_out
+};
+
+FC_HD int fc_floor_to(int x, int a) { int r = x % a; if (r < 0) r += a; return x - r; }
+FC_HD int fc_ceil_to(int x, int a) { return fc_floor_to(x + a - 1, a); }
+
+// Window [e_lo, e_hi) of extended channels that can hold a non-zero filter
+// entry for output columns [n_lo, n_hi), rounded outwards to `align`.
+FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int *e_lo, int *e_hi) {
+    int lo = g.e_min, hi = g.e_max;
+    if (g.band) {
+        if (n_hi > g.NCo) n_hi = g.NCo;
+        int g0 = n_lo / g.Co, g1 = (n_hi - 1) / g.Co;
+        int blo = fc_floor_to((g0 - g.pad_w) * g.C, align);
+        int bhi = fc_ceil_to((g1 + g.KW - g.pad_w) * g.C, align);
+        if (blo > lo) lo = blo;
+        if (bhi < hi) hi = bhi;
+        if (hi < lo) hi = lo;
+    }
+    *e_lo = lo;
+    *e_hi = hi;
+}
+
+enum { FC_KERNEL_GATHER = 0, FC_KERNEL_TILED = 1, FC_KERNEL_STREAM = 2 };
+
+struct foldconv_plan_s {
+    uint32_t magic;
+    foldconv_shapes_t s;
+    ConvGeom fold;  // the folded problem (band/relu/out_row/has_bias filled per call)
+    ConvGeom padc;  // the zero-padded problem, F = 1, C = C_pad
+    // byte offsets inside the padded-path workspace
+    size_t ws_xpad, ws_wpad, ws_wpack;
+};
+
+#define FOLDCONV_MAGIC 0xF01DC0DEu

@@ -1,0 +1,156 @@
+// Host-only part of libfoldconv: legality, closed forms of the folded
+// problem, workspace layout, kernel choice and FLOP accounting.
+// paper: Algorithm 1 (guard and the shapes of X_f, W_f', b'); the shapes in
+// "Width-Folding Transformation as an IR Transformation"; legality paragraph
+// of "Compiler-Level Realization in MLIR".
+#include <limits.h>
+#include <new>
+#include <string.h>
+
+#include "geom.h"
+#include "launch.h"
+
+static long long floor_div_ll(long long a, long long b) {
+    long long q = a / b;
+    if ((a % b) != 0 && ((a < 0) != (b < 0))) --q;
+    return q;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// MFMA flops issued by a kernel whose band window is taken per `tile_n`
+// output columns, in K-steps of `kstep` elements aligned to `align`.
+static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int align) {
+    g.band = band;
+    double total = 0.0;
+    for (int n0 = 0; n0 < g.NCo; n0 += tile_n) {
+        int n1 = n0 + tile_n < g.NCo ? n0 + tile_n : g.NCo;
+        int e_lo, e_hi;
+        fc_band_window(g, n0, n1, align, &e_lo, &e_hi);
+        long long steps = ((long long)(e_hi - e_lo) + kstep - 1) / kstep;
+        long long cols = ((n1 - n0) + 31) / 32 * 32;
+        total += 2.0 * (double)g.M * (double)cols * (double)(steps * kstep) * g.KH;
+    }
+    return total;
+}
+
+extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
+                             int fold_factor, foldconv_dtype_t dtype, foldconv_plan_t *out) {
+    if (!out) return FOLDCONV_ERR_BADARG;
+    *out = nullptr;
+    if (N <= 0 || H <= 0 || W <= 0 || C_in <= 0 || C_out <= 0 || KH <= 0 || KW <= 0 || pad < 0 ||
+        fold_factor <= 0)
+        return FOLDCONV_ERR_BADARG;
+    if (dtype != FOLDCONV_F32 && dtype != FOLDCONV_F16 && dtype != FOLDCONV_BF16)
+        return FOLDCONV_ERR_BADARG;
+    const int F = fold_factor;
+    if (W % F != 0) return FOLDCONV_ERR_INDIVISIBLE;  // Algorithm 1 guard
+
+    const int pad_h = KH > 1 ? pad : 0;
+    const int pad_w = KW > 1 ? pad : 0;
+    const long long H_out = (long long)H + 2 * pad_h - KH + 1;
+    const long long W_out = (long long)W + 2 * pad_w - KW + 1;
+    if (H_out <= 0 || W_out <= 0) return FOLDCONV_ERR_UNSUPPORTED;
+
+    const int eb = dtype == FOLDCONV_F32 ? 4 : 2;
+    const long long Wf = W / F;
+    const long long FC = (long long)F * C_in;
+    const long long FCo = (long long)F * C_out;
+    const long long d_min = floor_div_ll(-(long long)pad_w, F);
+    const long long d_max = floor_div_ll((long long)F + KW - 2 - pad_w, F);
+    const long long KWf = d_max - d_min + 1;
+    const long long Wf_out = (W_out + F - 1) / F;
+    const long long M = (long long)N * H_out * Wf_out;
+    const long long K = (long long)KH * KWf * FC;
+    const int C_pad = (C_in + 7) / 8 * 8;  // the alignment the paper names for fp16 tensor cores
+
+    // Limits of the kernels' 32-bit tile arithmetic.
+    const long long lim = (long long)INT_MAX / 4;
+    const long long M_pad = (long long)N * H_out * W_out;
+    if (Wf * FC > lim || FCo * Wf_out > lim || K > lim || KWf * FC > lim || M > lim * 2 || M_pad > lim * 2 ||
+        (long long)W * C_pad > lim || (long long)KH * KW * C_pad > lim)
+        return FOLDCONV_ERR_UNSUPPORTED;
+
+    foldconv_plan_s *p = new (std::nothrow) foldconv_plan_s;
+    if (!p) return FOLDCONV_ERR_BADARG;
+    memset(p, 0, sizeof(*p));
+    p->magic = FOLDCONV_MAGIC;
+    foldconv_shapes_t &s = p->s;
+    s.N = N; s.H = H; s.W = W; s.C_in = C_in; s.C_out = C_out; s.KH = KH; s.KW = KW; s.pad = pad;
+    s.F = F; s.dtype = (int)dtype; s.pad_h = pad_h; s.pad_w = pad_w;
+    s.W_fold = (int)Wf; s.C_fold = (int)FC; s.Co_fold = (int)FCo;
+    s.d_min = (int)d_min; s.d_max = (int)d_max; s.KW_fold = (int)KWf;
+    s.pad_left_fold = (int)-d_min;
+    s.pad_right_fold = (int)(Wf_out - Wf + d_min + KWf - 1);
+    s.H_out = (int)H_out; s.W_out = (int)W_out; s.W_out_fold = (int)Wf_out;
+    s.unfold_is_alias = (W_out == Wf_out * F) ? 1 : 0;
+    s.C_pad = C_pad; s.elem_bytes = eb;
+    s.gemm_M = M; s.gemm_N = FCo; s.gemm_K = K;
+    s.x_bytes = (long long)N * H * W * C_in * eb;
+    s.w_bytes = (long long)KH * KW * C_in * C_out * eb;
+    s.bias_bytes = (long long)C_out * eb;
+    s.w_exp_bytes = K * FCo * eb;
+    s.y_bytes = (long long)N * H_out * W_out * C_out * eb;
+    s.y_fold_bytes = M * FCo * eb;
+    s.useful_flops = 2.0 * (double)N * H_out * W_out * C_out * KH * KW * C_in;
+
+    ConvGeom &g = p->fold;
+    g.N = N; g.H = H; g.Hout = (int)H_out; g.Wf = (int)Wf; g.Wf_out = (int)Wf_out;
+    g.FC = (int)FC; g.NCo = (int)FCo; g.Co = C_out; g.C = C_in; g.F = F; g.KH = KH; g.KW = KW;
+    g.pad_h = pad_h; g.pad_w = pad_w;
+    g.e_min = (int)(d_min * FC); g.e_max = (int)((d_max + 1) * FC); g.kwin = g.e_max - g.e_min;
+    g.in_row = (int)(Wf * FC); g.out_row = (int)(W_out * C_out); g.M = M;
+
+    // Zero-padded reference problem: F = 1, every pixel C_pad channels.
+    ConvGeom &q = p->padc;
+    q.N = N; q.H = H; q.Hout = (int)H_out; q.Wf = W; q.Wf_out = (int)W_out;
+    q.FC = C_pad; q.NCo = C_out; q.Co = C_out; q.C = C_pad; q.F = 1; q.KH = KH; q.KW = KW;
+    q.pad_h = pad_h; q.pad_w = pad_w;
+    q.e_min = -pad_w * C_pad; q.e_max = (KW - pad_w) * C_pad; q.kwin = q.e_max - q.e_min;
+    q.in_row = W * C_pad; q.out_row = (int)(W_out * C_out); q.M = M_pad;
+
+    s.conv_kernel = fc_choose_kernel(g, dtype);
+    s.padded_kernel = fc_choose_kernel(q, dtype);
+
+    const long long xpad_bytes = (long long)N * H * W * C_pad * eb;
+    const long long wpad_bytes = (long long)KH * KW * C_pad * C_out * eb;
+    s.workspace_bytes = s.conv_kernel == FC_KERNEL_GATHER ? 0 : (long long)align_up((size_t)s.w_exp_bytes, 256);
+    p->ws_xpad = 0;
+    p->ws_wpad = align_up((size_t)xpad_bytes, 256);
+    p->ws_wpack = p->ws_wpad + align_up((size_t)wpad_bytes, 256);
+    s.padded_workspace_bytes =
+        (long long)(p->ws_wpack + (s.padded_kernel == FC_KERNEL_GATHER ? 0 : align_up((size_t)wpad_bytes, 256)));
+
+    const bool mfma16 = dtype != FOLDCONV_F32;
+    const int kstep = mfma16 ? 16 : 2;
+    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g), kstep, fc_band_align(s.conv_kernel, dtype));
+    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g), kstep, fc_band_align(s.conv_kernel, dtype));
+    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q), kstep, fc_band_align(s.padded_kernel, dtype));
+
+    *out = p;
+    return FOLDCONV_OK;
+}
+
+extern "C" int foldconv_plan_query(foldconv_plan_t plan, foldconv_shapes_t *out) {
+    if (!plan || plan->magic != FOLDCONV_MAGIC || !out) return FOLDCONV_ERR_BADARG;
+    *out = plan->s;
+    return FOLDCONV_OK;
+}
+
+extern "C" void foldconv_plan_destroy(foldconv_plan_t plan) {
+    if (!plan || plan->magic != FOLDCONV_MAGIC) return;
+    plan->magic = 0;
+    delete plan;
+}
+
+extern "C" const char *foldconv_strerror(int status) {
+    switch (status) {
+        case FOLDCONV_OK: return "ok";
+        case FOLDCONV_ERR_BADARG: return "bad argument";
+        case FOLDCONV_ERR_INDIVISIBLE: return "width is not divisible by the fold factor";
+        case FOLDCONV_ERR_UNSUPPORTED: return "unsupported problem (empty output or size beyond kernel limits)";
+        case FOLDCONV_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+        case FOLDCONV_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}

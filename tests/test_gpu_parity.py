@@ -1,0 +1,179 @@
+"""GPU parity: every step of the hot path, called through the C ABI, against
+the fp64 CPU oracle on the same seeded inputs.  Data movement must be
+bit-exact; convolution results must stay within the relative-L2 tolerances
+(fp16 2e-3, bf16 8e-3, fp32 1e-5; maximum over images)."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, TORCH_DT, bits, bits_as_f64, f64, rel_l2_per_image
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fc():
+    import paper_2601_11608_amd as fc
+
+    fc.load_library()          # raises if the HIP library is not built: there is no fallback
+    assert torch.cuda.is_available()
+    return fc
+
+
+def dev(t):
+    return None if t is None else t.cuda()
+
+
+def draw(shape, dt, seed, kind="normal"):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    t = torch.randn(shape, generator=g) if kind == "normal" else torch.rand(shape, generator=g) * 2 - 1
+    return t.to(TORCH_DT[dt])
+
+
+def run_folded(fc, plan, x, w, b, flags=0, separate_fold=False):
+    """expand -> fold -> forward through the ABI; returns y (CPU tensor)."""
+    s = plan.shapes
+    dt = x.dtype
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=dt, device="cuda")
+    fc.foldconv_expand_filter(plan, wd, w_exp)
+    if separate_fold:
+        x_fold = torch.empty_like(xd)
+        fc.foldconv_fold_input(plan, xd, x_fold)
+    else:
+        x_fold = xd
+        fc.foldconv_fold_input(plan, xd, x_fold)        # alias: legal no-op
+    ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+    if flags & fc.FLAG_KEEP_FOLDED:
+        y = torch.full((s.N, s.H_out, s.W_out_fold, s.Co_fold), float("nan"), dtype=dt, device="cuda")
+    else:
+        y = torch.full((s.N, s.H_out, s.W_out, s.C_out), float("nan"), dtype=dt, device="cuda")
+    fc.foldconv_forward(plan, x_fold, w_exp, bd, y, ws, flags)
+    torch.cuda.synchronize()
+    return y.cpu()
+
+
+def run_padded(fc, plan, x, w, b, flags=0):
+    s = plan.shapes
+    ws = torch.empty(max(int(s.padded_workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+    y = torch.full((s.N, s.H_out, s.W_out, s.C_out), float("nan"), dtype=x.dtype, device="cuda")
+    fc.conv_padded_forward(plan, dev(x), dev(w), dev(b), y, ws, flags)
+    torch.cuda.synchronize()
+    return y.cpu()
+
+
+# N, H, W, C, Co, KH, KW, pad, F, bias, relu  -- several tiles plus ragged tails in m and n
+SMALL = [
+    (2, 9, 24, 3, 5, 3, 3, 1, 8, True, False),      # FC=24, n ragged (40), m ragged (54)
+    (1, 32, 32, 3, 16, 3, 3, 1, 8, False, False),   # the small fp32 benchmark layer
+    (3, 7, 32, 3, 64, 3, 3, 1, 16, True, True),     # headline layer's structure, tiny
+    (2, 12, 16, 12, 48, 3, 3, 1, 4, False, True),   # FC=48, NCo=192
+    (2, 1, 256, 1, 64, 1, 9, 4, 32, False, False),  # Conv1d
+    (1, 40, 64, 1, 1, 5, 1, 0, 8, True, False),     # the paper's K x 1 / VALID listing shape
+    (1, 6, 12, 2, 3, 3, 3, 0, 4, True, False),      # VALID: ragged W_out (10)
+    (1, 5, 12, 2, 2, 2, 4, 2, 4, False, False),     # even kernel, W_out = 13 > W
+    (2, 5, 7, 3, 3, 3, 3, 1, 1, True, True),        # F = 1, unaligned channels
+    (1, 9, 16, 20, 36, 3, 3, 1, 4, False, True),    # FC=80
+    (1, 6, 8, 36, 68, 3, 3, 1, 4, False, False),    # FC=144, NCo=272
+    (1, 3, 64, 1, 8, 1, 3, 1, 64, True, False),     # F == W
+    (1, 4, 16, 5, 7, 1, 1, 0, 8, True, False),      # 1x1 (GEMM as conv), FC=40
+]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "x".join(map(str, c[:9])))
+def test_forward_small_matches_oracle(fc, oracle, case, dt):
+    N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
+    x = draw((N, H, W, C), dt, 1)
+    w = draw((KH, KW, C, Co), dt, 2) * (1.0 / np.sqrt(KH * KW * C))
+    w = w.to(TORCH_DT[dt])
+    b = draw((Co,), dt, 3) if hb else None
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    ref = oracle.conv_direct(f64(x), f64(w), None if b is None else f64(b), ph, pw, relu)
+    plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, x.dtype)
+    rflag = fc.FLAG_RELU if relu else 0
+    y_band = run_folded(fc, plan, x, w, b, rflag)
+    assert rel_l2_per_image(f64(y_band), ref) <= TOL[dt]
+    y_dense = run_folded(fc, plan, x, w, b, rflag | fc.FLAG_DENSE_K, separate_fold=True)
+    assert rel_l2_per_image(f64(y_dense), ref) <= TOL[dt]
+    # skipping structural zeros only drops exact-zero products
+    assert np.array_equal(bits(y_band), bits(y_dense))
+    # folded layout + explicit reconstruct == fused reconstruct, bit for bit
+    y_fold = run_folded(fc, plan, x, w, b, rflag | fc.FLAG_KEEP_FOLDED)
+    s = plan.shapes
+    y2 = torch.full((N, s.H_out, s.W_out, Co), float("nan"), dtype=x.dtype, device="cuda")
+    fc.foldconv_unfold_output(plan, y_fold.cuda(), y2)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(y2), bits(y_band))
+    want = oracle.unfold_output(bits_as_f64(y_fold), F, Co, s.W_out)
+    assert np.array_equal(bits_as_f64(y2), want)
+    # zero-padded reference path
+    y_pad = run_padded(fc, plan, x, w, b, rflag)
+    assert rel_l2_per_image(f64(y_pad), ref) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("KH,KW,C,Co,F,pad", [(3, 3, 3, 64, 16, 1), (1, 9, 1, 64, 32, 4), (5, 1, 1, 1, 8, 0),
+                                               (3, 3, 12, 48, 4, 1), (2, 4, 2, 3, 4, 2), (3, 3, 3, 5, 1, 1),
+                                               (3, 3, 132, 256, 4, 1)])
+def test_expand_filter_bit_exact(fc, oracle, KH, KW, C, Co, F, pad, dt):
+    w = draw((KH, KW, C, Co), dt, 11)
+    plan = fc.foldconv_plan(1, 8, 8 * F, C, Co, KH, KW, pad, F, w.dtype)
+    s = plan.shapes
+    w_exp = torch.full((KH, s.KW_fold, F * C, F * Co), float("nan"), dtype=w.dtype, device="cuda")
+    fc.foldconv_expand_filter(plan, w.cuda(), w_exp)
+    torch.cuda.synchronize()
+    want = oracle.expand_filter(bits_as_f64(w), F, s.pad_w)     # zeros are bit pattern 0 == +0.0
+    assert np.array_equal(bits_as_f64(w_exp), want)
+
+
+@pytest.mark.parametrize("dt", ["f16", "f32"])
+@pytest.mark.parametrize("N,H,W,C,F", [(2, 5, 48, 3, 16), (1, 1, 16000, 1, 32), (3, 7, 20, 5, 4), (1, 3, 6, 1, 2)])
+def test_fold_input_bit_exact(fc, oracle, N, H, W, C, F, dt):
+    x = draw((N, H, W, C), dt, 12)
+    plan = fc.foldconv_plan(N, H, W, C, 4, 1, 1, 0, F, x.dtype)
+    xf = torch.full((N, H, W // F, F * C), float("nan"), dtype=x.dtype, device="cuda")
+    fc.foldconv_fold_input(plan, x.cuda(), xf)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_as_f64(xf), oracle.fold_input(bits_as_f64(x), F))
+
+
+def test_fold_input_unaligned_pointers(fc, oracle):
+    """Odd byte offsets take the byte-wise copy."""
+    x = draw((1, 3, 8, 3), "f16", 13)
+    plan = fc.foldconv_plan(1, 3, 8, 3, 4, 1, 1, 0, 4, x.dtype)
+    buf_in = torch.zeros(x.numel() + 8, dtype=x.dtype, device="cuda")
+    buf_out = torch.zeros(x.numel() + 8, dtype=x.dtype, device="cuda")
+    buf_in[1:1 + x.numel()] = x.cuda().flatten()
+    fc.foldconv_fold_input(plan, buf_in.data_ptr() + 2, buf_out.data_ptr() + 6)
+    torch.cuda.synchronize()
+    got = buf_out[3:3 + x.numel()].reshape(1, 3, 2, 12)
+    assert np.array_equal(bits_as_f64(got), oracle.fold_input(bits_as_f64(x), 4))
+    assert float(buf_out[:3].abs().sum()) == 0 and float(buf_out[3 + x.numel():].abs().sum()) == 0
+
+
+def test_runtime_argument_errors(fc):
+    plan = fc.foldconv_plan(1, 6, 12, 2, 3, 3, 3, 0, 4, torch.float16)     # ragged: unfold is not an alias
+    s = plan.shapes
+    assert s.unfold_is_alias == 0
+    yf = torch.zeros(s.y_fold_bytes // 2, dtype=torch.float16, device="cuda")
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_unfold_output(plan, yf, yf)
+    assert e.value.status == -1
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.conv_padded_forward(plan, yf, yf, None, yf, torch.zeros(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -4
+
+
+def test_empty_bias_and_relu_flags(fc, oracle):
+    """b = const, w = 0 -> y == b (paper: Eq. bias_construct); ReLU clamps."""
+    N, H, W, C, Co, F = 1, 4, 16, 3, 4, 8
+    x = draw((N, H, W, C), "f16", 14)
+    w = torch.zeros((3, 3, C, Co), dtype=torch.float16)
+    b = torch.tensor([0.5, -1.25, 2.0, -0.0], dtype=torch.float16)
+    plan = fc.foldconv_plan(N, H, W, C, Co, 3, 3, 1, F, x.dtype)
+    y = run_folded(fc, plan, x, w, b, 0)
+    assert torch.equal(y, b.expand(N, H, W, Co))
+    y = run_folded(fc, plan, x, w, b, fc.FLAG_RELU)
+    assert torch.equal(y, torch.relu(b).expand(N, H, W, Co))

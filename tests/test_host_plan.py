@@ -1,0 +1,161 @@
+"""Host-side checks that need no GPU: the C-ABI library loads and exports
+every declared symbol, the plan's closed forms agree with the oracle's (which
+are pinned by enumeration), error paths, and struct layout."""
+import ctypes
+import os
+import re
+import subprocess
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "foldconv.h")
+
+
+@pytest.fixture(scope="module")
+def fc():
+    import paper_2601_11608_amd as fc
+
+    if not os.path.exists(fc.library_path()):
+        from paper_2601_11608_amd import build
+
+        build.build()
+    fc.load_library()
+    return fc
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    return re.findall(r"FOLDCONV_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)
+
+
+def test_library_exports_every_declared_symbol(fc):
+    names = declared_functions()
+    assert set(names) >= {"foldconv_plan", "foldconv_plan_query", "foldconv_plan_destroy", "foldconv_expand_filter",
+                          "foldconv_fold_input", "foldconv_unfold_output", "foldconv_pack_filter",
+                          "foldconv_forward", "conv_padded_forward", "foldconv_strerror"}
+    lib = ctypes.CDLL(fc.library_path())
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    # and the binding offers each of them under the same name
+    for n in names:
+        assert hasattr(fc, n), n
+
+
+def test_no_internal_symbols_leak(fc):
+    out = subprocess.check_output(["nm", "-D", "--defined-only", fc.library_path()], text=True)
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l}
+    assert exported == set(declared_functions())
+
+
+def test_shapes_struct_layout_matches_c(fc):
+    from paper_2601_11608_amd.binding import Shapes
+
+    src = '#include <stdio.h>\n#include <stddef.h>\n#include "foldconv.h"\nint main(){printf("%zu %zu %zu\\n", sizeof(foldconv_shapes_t), offsetof(foldconv_shapes_t, gemm_M), offsetof(foldconv_shapes_t, useful_flops));return 0;}\n'
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "s.c")
+        open(c, "w").write(src)
+        exe = os.path.join(d, "s")
+        subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), c, "-o", exe])
+        size, off_m, off_f = map(int, subprocess.check_output([exe], text=True).split())
+    assert ctypes.sizeof(Shapes) == size
+    assert Shapes.gemm_M.offset == off_m
+    assert Shapes.useful_flops.offset == off_f
+
+
+PLAN_CASES = [
+    # N,H,W,C,Co,KH,KW,pad,F
+    (1, 32, 32, 3, 16, 3, 3, 1, 8),
+    (64, 224, 224, 3, 64, 3, 3, 1, 16),
+    (32, 112, 112, 12, 48, 3, 3, 1, 4),
+    (16, 1, 16000, 1, 64, 1, 9, 4, 32),
+    (32, 112, 112, 132, 256, 3, 3, 1, 4),
+    (1, 32, 64, 1, 1, 5, 1, 0, 8),
+    (1, 6, 12, 2, 3, 3, 3, 0, 4),
+    (1, 4, 12, 2, 2, 2, 4, 2, 4),
+    (2, 5, 7, 3, 3, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("N,H,W,C,Co,KH,KW,pad,F", PLAN_CASES)
+def test_plan_closed_forms_match_oracle(fc, oracle, N, H, W, C, Co, KH, KW, pad, F):
+    p = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, "float16")
+    s = p.shapes
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    assert (s.pad_h, s.pad_w) == (ph, pw)
+    sh = oracle.folded_shapes(W, KW, pw, F)
+    assert (s.W_fold, s.d_min, s.d_max, s.KW_fold) == (sh["Wf"], sh["d_min"], sh["d_max"], sh["KWf"])
+    assert (s.W_out, s.W_out_fold) == (sh["W_out"], sh["Wf_out"])
+    assert (s.pad_left_fold, s.pad_right_fold) == (sh["pad_left_f"], sh["pad_right_f"])
+    assert s.H_out == H + 2 * ph - KH + 1
+    assert (s.C_fold, s.Co_fold) == (F * C, F * Co)
+    assert s.gemm_M == N * s.H_out * s.W_out_fold and s.gemm_N == F * Co and s.gemm_K == KH * s.KW_fold * F * C
+    assert s.w_exp_bytes == s.gemm_K * s.gemm_N * 2
+    assert s.x_bytes == N * H * W * C * 2 and s.y_bytes == N * s.H_out * s.W_out * Co * 2
+    assert s.y_fold_bytes == s.gemm_M * s.gemm_N * 2
+    assert s.unfold_is_alias == int(s.W_out == F * s.W_out_fold)
+    assert s.useful_flops == 2.0 * N * s.H_out * s.W_out * Co * KH * KW * C
+    assert s.C_pad % 8 == 0 and 0 <= s.C_pad - C < 8
+    assert s.issued_flops_band <= s.issued_flops_dense
+    assert s.issued_flops_band >= s.useful_flops * 0.999
+    p.destroy()
+
+
+def test_headline_layer_numbers(fc):
+    """Sizes of the 224x224 C_in = 3 first layer, F = 16."""
+    s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
+    assert (s.W_fold, s.C_fold, s.Co_fold, s.KW_fold) == (14, 48, 1024, 3)
+    assert (s.gemm_M, s.gemm_N, s.gemm_K) == (200704, 1024, 432)
+    assert s.y_bytes == 411041792 and s.unfold_is_alias == 1
+    assert abs(s.useful_flops - 11.098e9) < 1e7
+    assert abs(s.issued_flops_dense - 177.57e9) < 1e8
+
+
+def test_plan_errors(fc):
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_plan(1, 8, 10, 3, 4, 3, 3, 1, 4, "float16")
+    assert e.value.status == -2                      # Algorithm 1 guard: W mod F != 0
+    for bad in [(0, 8, 8, 3, 4, 3, 3, 1, 4), (1, 8, 8, 0, 4, 3, 3, 1, 4), (1, 8, 8, 3, 4, 3, 3, -1, 4),
+                (1, 8, 8, 3, 4, 3, 3, 1, 0)]:
+        with pytest.raises(fc.FoldconvError) as e:
+            fc.foldconv_plan(*bad, "float16")
+        assert e.value.status == -1
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_plan(1, 2, 8, 3, 4, 5, 3, 0, 4, "float16")   # VALID kernel taller than the image
+    assert e.value.status == -3
+    lib = fc.load_library()
+    assert lib.foldconv_plan(1, 8, 8, 3, 4, 3, 3, 1, 4, 7, ctypes.byref(ctypes.c_void_p())) == -1   # unknown dtype
+    assert lib.foldconv_plan(1, 8, 8, 3, 4, 3, 3, 1, 4, 1, None) == -1
+    assert lib.foldconv_plan_query(None, None) == -1
+    lib.foldconv_plan_destroy(None)
+    for code in range(-6, 1):
+        assert isinstance(fc.foldconv_strerror(code), str) and fc.foldconv_strerror(code)
+
+
+def test_null_pointer_calls_are_rejected_without_gpu(fc):
+    """Argument checks come before any HIP call, so they can run on a CPU-only host."""
+    lib = fc.load_library()
+    p = fc.foldconv_plan(1, 8, 8, 3, 4, 3, 3, 1, 4, "float16")
+    h = p.handle
+    assert lib.foldconv_expand_filter(h, None, None, None) == -1
+    assert lib.foldconv_fold_input(h, None, None, None) == -1
+    assert lib.foldconv_unfold_output(h, None, None, None) == -1
+    assert lib.foldconv_forward(h, None, None, None, None, None, 0, 0, None) == -1
+    assert lib.conv_padded_forward(h, None, None, None, None, None, 0, 0, None) == -1
+    assert lib.foldconv_forward(h, 256, 512, None, 1024, None, 0, 1 << 20, None) == -1     # unknown flag
+    assert lib.conv_padded_forward(h, 256, 512, None, 1024, None, 0, 0, None) == -4        # workspace missing
+    assert lib.foldconv_fold_input(h, 4096, 4096, None) == 0                               # alias: nothing to do
+    assert lib.foldconv_fold_input(h, 4096, 4096 + 16, None) == -1                         # partial overlap
+
+
+def test_workloads_shapes():
+    from paper_2601_11608_amd import workloads as wl
+
+    assert [l.F for l in wl.CONFIGS["c5"]] == [16, 4, 4, 4, 4]
+    layers, x, ws, bs = wl.make_config("c1")
+    assert tuple(x.shape) == (1, 32, 32, 3) and tuple(ws[0].shape) == (3, 3, 3, 16) and bs[0] is None
+    layers, x, ws, bs = wl.make_config("c4", N=2)
+    assert tuple(x.shape) == (2, 1, 16000, 1) and tuple(ws[0].shape) == (1, 9, 1, 64)
+    layers, x2, ws2, _ = wl.make_config("c4", N=2)
+    assert (x2 == x).all() and (ws2[0] == ws[0]).all()      # seeded
