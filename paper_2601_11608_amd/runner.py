@@ -1,0 +1,70 @@
+"""Per-layer and per-stack call sequences over the C ABI (buffer ownership and
+call order only; all computation happens inside libfoldconv's kernels)."""
+import torch
+
+from . import binding as fc
+
+
+class FoldedLayer:
+    """One convolution layer prepared once (plan, expanded + packed filter) and
+    then run many times, as the paper's post-training rewrite intends."""
+
+    def __init__(self, layer, w, b, device="cuda"):
+        self.layer = layer
+        self.dtype = w.dtype
+        self.plan = fc.foldconv_plan(*layer.plan_args(), w.dtype)
+        s = self.plan.shapes
+        self.w = w.to(device).contiguous()
+        self.b = None if b is None else b.to(device).contiguous()
+        self.w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=w.dtype, device=device)
+        fc.foldconv_expand_filter(self.plan, self.w, self.w_exp)
+        self.ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device=device)
+        fc.foldconv_pack_filter(self.plan, self.w_exp, self.ws)
+        self.ws_pad = None
+        self.pad_ready = False
+
+    def out_shape(self):
+        s = self.plan.shapes
+        return (s.N, s.H_out, s.W_out, s.C_out)
+
+    def new_output(self):
+        return torch.empty(self.out_shape(), dtype=self.dtype, device=self.w.device)
+
+    def forward(self, x, y, flags=0, repack=False):
+        """fold (aliased: x' shares x's bytes) + folded convolution + fused reconstruct."""
+        fc.foldconv_fold_input(self.plan, x, x)
+        if self.layer.relu:
+            flags |= fc.FLAG_RELU
+        if not repack:
+            flags |= fc.FLAG_FILTER_PACKED
+        fc.foldconv_forward(self.plan, x, self.w_exp, self.b, y, self.ws, flags)
+        return y
+
+    def forward_padded(self, x, y, repack=False):
+        s = self.plan.shapes
+        if self.ws_pad is None:
+            self.ws_pad = torch.empty(max(int(s.padded_workspace_bytes), 256), dtype=torch.uint8, device=self.w.device)
+        flags = fc.FLAG_RELU if self.layer.relu else 0
+        if self.pad_ready and not repack:
+            flags |= fc.FLAG_FILTER_PACKED
+        fc.conv_padded_forward(self.plan, x, self.w, self.b, y, self.ws_pad, flags)
+        self.pad_ready = True
+        return y
+
+
+class FoldedStack:
+    """A chain of layers; each output buffer is the next layer's (aliased) folded input."""
+
+    def __init__(self, layers, ws, bs, device="cuda"):
+        self.layers = [FoldedLayer(l, w, b, device) for l, w, b in zip(layers, ws, bs)]
+        self.outs = [l.new_output() for l in self.layers]
+
+    def forward(self, x, flags=0, padded=False):
+        a = x
+        for l, y in zip(self.layers, self.outs):
+            if padded:
+                l.forward_padded(a, y)
+            else:
+                l.forward(a, y, flags)
+            a = y
+        return a
