@@ -3,8 +3,13 @@
 
 int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp,
                    const void *w_pack, const void *bias, void *y, void *stream) {
-    (void)w_pack;
     switch (kernel) {
+        case FC_KERNEL_STREAM: {
+            // The dense walk may need more K-steps than any streaming instance holds.
+            StreamShape sh;
+            if (fc_stream_shape(g, g.band, &sh)) return fc_launch_conv_stream(dt, g, x, w_pack, bias, y, stream);
+            return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);
+        }
         case FC_KERNEL_GATHER:
         default:
             return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);

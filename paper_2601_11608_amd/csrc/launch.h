@@ -11,9 +11,15 @@ int fc_band_align(int kernel, foldconv_dtype_t dt); // alignment of the band win
 
 // Shape of the streaming kernel instance for a geometry; false if none fits.
 struct StreamShape {
+    int inst;    // index into FC_STREAM_INSTANCES
     int nt;      // 32-column MFMA tiles held per wave
-    int ksteps;  // 16-wide K-steps per kh held per wave
+    int ksteps;  // 16-wide K-steps per kh actually walked
 };
+// Compiled instances of the streaming kernel: X(NT, max KH, max K-steps per kh, workgroups per CU).
+// Filter fragments cost 4*NT*KH*ksteps registers per lane, which bounds the list.
+#define FC_STREAM_INSTANCES(X) \
+    X(4, 1, 2, 2) X(4, 3, 2, 2) X(2, 1, 2, 2) X(2, 1, 6, 2) X(2, 3, 1, 2) X(2, 3, 2, 2) X(2, 3, 4, 2) X(2, 5, 1, 2) \
+    X(2, 3, 9, 1) X(1, 3, 12, 1)
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 
 // --- launchers (return 0 or a hipError_t value) -------------------------------
@@ -27,5 +33,7 @@ int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const voi
                    const void *w_pack, const void *bias, void *y, void *stream);
 
 // Per-kernel launchers behind fc_launch_conv.
+int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
+                          void *y, void *stream);
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,
                           void *y, void *stream);

@@ -1,20 +1,60 @@
 // Which convolution kernel serves a geometry, and the tiling facts the plan
 // needs for FLOP accounting.  Host only.
+#include <stdlib.h>
+
 #include "launch.h"
+
+namespace {
+struct Inst { int nt, khm, ksm, occ; };
+#define FC_ROW(NT_, KHM_, KSM_, OCC_) {NT_, KHM_, KSM_, OCC_},
+const Inst kInst[] = {FC_STREAM_INSTANCES(FC_ROW)};
+#undef FC_ROW
+const int kNumInst = (int)(sizeof(kInst) / sizeof(kInst[0]));
+
+int max_ksteps(ConvGeom g, int band, int cols) {
+    g.band = band;
+    int worst = 0;
+    for (int n0 = 0; n0 < g.NCo; n0 += cols) {
+        int e_lo, e_hi;
+        fc_band_window(g, n0, n0 + cols, 8, &e_lo, &e_hi);
+        int k = (e_hi - e_lo + 15) / 16;
+        if (k > worst) worst = k;
+    }
+    return worst;
+}
+}  // namespace
+
+bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
+    // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of 8.
+    if (g.FC % 8 != 0 || g.NCo % 8 != 0 || g.out_row % 8 != 0 || g.kwin % 8 != 0) return false;
+    static const int prefer[] = {4, 2, 1};
+    for (int nt : prefer) {
+        const int ks = max_ksteps(g, band, 32 * nt);
+        for (int i = 0; i < kNumInst; ++i)
+            if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
+                out->inst = i;
+                out->nt = nt;
+                out->ksteps = ks;
+                return true;
+            }
+    }
+    return false;
+}
 
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt) {
     // fp32 and channel counts that miss the 16-byte chunk alignment run the
     // element-gather MFMA kernel (the analogue of Algorithm 1's fallback: it is
     // correct for every shape, just not fast).
     if (dt == FOLDCONV_F32) return FC_KERNEL_GATHER;
-    if (g.FC % 8 != 0) return FC_KERNEL_GATHER;
+    StreamShape sh;
+    if (fc_stream_shape(g, 1, &sh)) return FC_KERNEL_STREAM;
     return FC_KERNEL_GATHER;
 }
 
-bool fc_stream_shape(const ConvGeom &, int, StreamShape *) { return false; }
-
-int fc_band_tile_n(int kernel, const ConvGeom &) {
+int fc_band_tile_n(int kernel, const ConvGeom &g) {
+    StreamShape sh;
     switch (kernel) {
+        case FC_KERNEL_STREAM: return fc_stream_shape(g, 1, &sh) ? 32 * sh.nt : 32;
         case FC_KERNEL_TILED: return 128;
         default: return 32;
     }
