@@ -20,6 +20,7 @@
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "launch.h"
 #include "mfma_types.h"
@@ -54,13 +55,23 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 struct StreamArgs {
-    long long MT;  // number of 32-pixel M tiles
-    int NG;        // column groups of NT*32 columns
-    long long J;   // M tiles in flight = stride of a wave's M-tile walk
-    int ksteps;    // 16-wide K-steps per kh actually walked (<= KSM)
+    unsigned MT;        // number of 32-pixel M tiles
+    unsigned J;         // M tiles in flight = stride of a wave's M-tile walk
+    int NG;             // column groups of NT*32 columns
+    int ksteps;         // 16-wide K-steps per kh actually walked (<= KSM)
+    unsigned dW, dH, dI;  // the walk stride of 32*J pixels as (folded column, row, image) steps
+    unsigned mgW, mgH;  // ceil(2^32 / Wf_out), ceil(2^32 / Hout): exact division of small numerators
+    unsigned x_bytes;   // extent of x for the range-checked buffer loads
+    int linear_out;     // stored rows are exactly Wf_out*NCo long: y offset is m*NCo + n
 };
 
-template <typename TR, int NT, int KHM, int KSM, int OCC>
+// floor(t / d) for t < d + 64 and d < 65000, with mg = ceil(2^32 / d)
+__device__ __forceinline__ unsigned small_div(unsigned t, unsigned mg, unsigned d) {
+    return d == 1u ? t : __umulhi(t, mg);
+}
+
+// EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
+template <typename TR, int NT, int KHM, int KSM, int OCC, bool EXACT, bool RELU>
 __global__ void __launch_bounds__(256, OCC)
 conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                    const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
@@ -69,24 +80,27 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     constexpr int COLS = 32 * NT;                 // output columns per wave
     constexpr int PITCH = COLS * 2 + 16;          // bytes per LDS row (padded)
     constexpr int CHUNKS = COLS / 8;              // 16-byte chunks per row
-    constexpr int SLAB = 32 * PITCH + 32 * 8;     // + per-row {offset/8, room} words
+    constexpr int PASSES = (32 * CHUNKS + 63) / 64;
+    constexpr int SLAB = 32 * PITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * SLAB];
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, hf = lane >> 5;
     unsigned char *slab = lds_all + wave * SLAB;
-    unsigned *rowinfo = reinterpret_cast<unsigned *>(slab + 32 * PITCH);
 
-    const long long gw = (long long)blockIdx.x * 4 + wave;
-    const int ng = (int)(gw % a.NG);
-    const long long j0 = gw / a.NG;
+    const unsigned gw = blockIdx.x * 4 + wave;
+    const int ng = (int)(gw % (unsigned)a.NG);
+    const unsigned j0 = gw / (unsigned)a.NG;
     if (j0 >= a.J) return;  // wave-uniform
 
+    const int KH = EXACT ? KHM : g.KH;
+    const int KS = EXACT ? KSM : a.ksteps;
     const int n_lo = ng * COLS;
     int e_lo, e_hi;
     fc_band_window(g, n_lo, n_lo + COLS, 8, &e_lo, &e_hi);
     const int q_per_kh = g.kwin / 8;
+    const int e0 = e_lo + 8 * hf;  // this lane's extended channel at K-step 0
 
     // ---- filter fragments, resident for the kernel's lifetime -----------------
     Vec wf[KHM][KSM][NT];
@@ -96,10 +110,10 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int ks = 0; ks < KSM; ++ks)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int e = e_lo + 16 * ks + 8 * hf;
+                const int e = e0 + 16 * ks;
                 const int n = n_lo + 32 * nt + r;
                 u32x4 v = {0u, 0u, 0u, 0u};
-                if (kh < g.KH && ks < a.ksteps && e < e_hi && n < g.NCo)
+                if (kh < KH && ks < KS && e < e_hi && n < g.NCo)
                     v = wp[((long long)kh * q_per_kh + ((e - g.e_min) >> 3)) * g.NCo + n];
                 wf[kh][ks][nt] = __builtin_bit_cast(Vec, v);
             }
@@ -116,44 +130,83 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         if (g.has_bias && hf == 0 && n < g.NCo) bf[nt][0] = bias[n % g.Co];
     }
 
-    // ---- per-tile input fragment loads ---------------------------------------
-    Vec xf[KHM][KSM];
-    unsigned my_off8, my_room;  // this lane's output row: (element offset)/8 and columns left in the row
-    auto load_tile = [&](long long mt, Vec (&dst)[KHM][KSM], unsigned &off8, unsigned &room) {
-        const long long m = mt * 32 + r;
-        const bool vm = m < g.M;
-        const long long mm = vm ? m : 0;
-        const int wo = (int)(mm % g.Wf_out);
-        const long long rowid = mm / g.Wf_out;
-        const int ho = (int)(rowid % g.Hout);
-        const long long img = rowid / g.Hout;
-        const int e0 = e_lo + 8 * hf;            // this lane's extended channel at K-step 0
-        const int col0 = wo * g.FC + e0;         // and its column inside the input row
-        const T *base = x + (img * g.H + ho - g.pad_h) * (long long)g.in_row + col0;
-        const int oc = wo * g.NCo;
-        off8 = (unsigned)((rowid * g.out_row + oc) >> 3);
-        room = vm && oc < g.out_row ? (unsigned)(g.out_row - oc) : 0u;
+    // Input fragments come through a range-checked buffer resource: a lane whose
+    // fragment lies outside the image (zero padding) uses an offset beyond the
+    // extent and receives zeros, with no branch and no select afterwards.
+    const __amdgpu_buffer_rsrc_t xr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(x), 0, (int)a.x_bytes, 0x00020000);
+    constexpr unsigned kOutOfRange = 0x80000000u;
+
+    // ---- the wave's current tile: first pixel m0 = (img0, ho0, wo0), advanced incrementally ----
+    unsigned m0 = j0 * 32u;
+    unsigned wo0 = m0 % (unsigned)g.Wf_out;
+    unsigned ho0, img0;
+    {
+        const unsigned rowid = m0 / (unsigned)g.Wf_out;
+        ho0 = rowid % (unsigned)g.Hout;
+        img0 = rowid / (unsigned)g.Hout;
+    }
+    // K-steps whose chunk lies inside this wave's band window (loop invariant per lane)
+    unsigned ksmask = 0;
+#pragma unroll
+    for (int ks = 0; ks < KSM; ++ks)
+        if (ks < KS && e0 + 16 * ks < e_hi) ksmask |= 1u << ks;
+
+    // per-lane constants of the row-wise store phase
+    int st_row[PASSES], st_n8[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int idx = p * 64 + lane;
+        st_row[p] = idx / CHUNKS;
+        st_n8[p] = (n_lo >> 3) + (idx - st_row[p] * CHUNKS);
+    }
+
+    u32x4 xf[KHM][KSM];
+    auto load_tile = [&](u32x4 (&dst)[KHM][KSM]) {
+        const unsigned t = wo0 + (unsigned)r;
+        const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
+        const unsigned wo = t - q * (unsigned)g.Wf_out;
+        const unsigned hr = ho0 + q;
+        const unsigned q2 = small_div(hr, a.mgH, (unsigned)g.Hout);
+        const unsigned ho = hr - q2 * (unsigned)g.Hout;
+        const unsigned img = img0 + q2;
+        const bool vm = m0 + (unsigned)r < (unsigned)g.M;
+        const int col0 = (int)wo * g.FC + e0;  // column of K-step 0 inside the input row
+        const int pix0 = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col0;  // element offset in x
+        unsigned colok = 0;
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks) {
+            const int col = col0 + 16 * ks;
+            if (((ksmask >> ks) & 1u) && col >= 0 && col < g.in_row) colok |= 1u << ks;
+        }
 #pragma unroll
         for (int kh = 0; kh < KHM; ++kh) {
-            const int hi = ho + kh - g.pad_h;
-            const bool rv = vm && kh < g.KH && hi >= 0 && hi < g.H;
+            const int hi = (int)ho + kh - g.pad_h;
+            const bool rv = vm && kh < KH && hi >= 0 && hi < g.H;
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks) {
-                const int col = col0 + 16 * ks;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                // in-bounds: row hi exists, and the 8-element chunk [col, col+8) lies inside it
+                // in range: row hi exists and the 8-element chunk [col, col+8) lies inside it
                 // (col and in_row are multiples of 8)
-                if (rv && ks < a.ksteps && e0 + 16 * ks < e_hi && col >= 0 && col < g.in_row)
-                    v = *reinterpret_cast<const u32x4 *>(base + (long long)kh * g.in_row + 16 * ks);
-                dst[kh][ks] = __builtin_bit_cast(Vec, v);
+                const bool ok = rv && ((colok >> ks) & 1u);
+                const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRange;
+                dst[kh][ks] = __builtin_amdgcn_raw_buffer_load_b128(xr, voff, 0, 0);
             }
         }
     };
+    auto advance = [&]() {
+        m0 += a.J * 32u;
+        wo0 += a.dW;
+        unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
+        wo0 -= c * (unsigned)g.Wf_out;
+        ho0 += a.dH + c;
+        c = ho0 >= (unsigned)g.Hout ? 1u : 0u;
+        ho0 -= c * (unsigned)g.Hout;
+        img0 += a.dI + c;
+    };
 
-    long long mt = j0;
-    load_tile(mt, xf, my_off8, my_room);
+    load_tile(xf);
 
-    for (; mt < a.MT; mt += a.J) {
+    for (unsigned mt = j0; mt < a.MT; mt += a.J) {
         floatx16_t acc[NT];
         floatx16_t zero;
 #pragma unroll
@@ -164,70 +217,104 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int kh = 0; kh < KHM; ++kh)
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks)
-                if (kh < g.KH && ks < a.ksteps) {
+                if (EXACT || (kh < KH && ks < KS)) {
+                    const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xf[kh][ks], acc[nt]);
+                    for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
                 }
 
-        const unsigned cur_off8 = my_off8, cur_room = my_room;
-        if (mt + a.J < a.MT) load_tile(mt + a.J, xf, my_off8, my_room);  // prefetch the next tile's input
+        // where this tile's rows go (wave-uniform part), then move on and prefetch
+        const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_rowid0 = img0 * (unsigned)g.Hout + ho0;
+        advance();
+        if (mt + a.J < a.MT) load_tile(xf);  // the next tile's input stays in flight across the epilogue
 
-        // ---- epilogue: ReLU, round, transpose through LDS, row-contiguous stores ----
-        if (hf == 0) {
-            rowinfo[2 * r] = cur_off8;
-            rowinfo[2 * r + 1] = cur_room;
-        }
+        // ---- epilogue: round, ReLU, transpose through LDS, row-contiguous stores ----
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float v0 = acc[nt][4 * q], v1 = acc[nt][4 * q + 1], v2 = acc[nt][4 * q + 2], v3 = acc[nt][4 * q + 3];
-                if (g.relu) {
-                    v0 = v0 > 0.0f ? v0 : 0.0f;
-                    v1 = v1 > 0.0f ? v1 : 0.0f;
-                    v2 = v2 > 0.0f ? v2 : 0.0f;
-                    v3 = v3 > 0.0f ? v3 : 0.0f;
+                u32x2 pk = {pack2<TR>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2<TR>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
+                if (RELU) {
+                    // max(v, 0) on the rounded 16-bit patterns as signed integers: negative
+                    // values (sign bit set) become +0, everything else is unchanged
+                    typedef short s16x4 __attribute__((ext_vector_type(4)));
+                    const s16x4 z = {0, 0, 0, 0};
+                    pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
                 }
-                u32x2 pk = {pack2<TR>(v0, v1), pack2<TR>(v2, v3)};
                 *reinterpret_cast<u32x2 *>(slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * 2) = pk;
             }
         wave_lds_sync();
 #pragma unroll
-        for (int idx0 = 0; idx0 < 32 * CHUNKS; idx0 += 64) {
-            const int idx = idx0 + lane;
-            const int row = idx / CHUNKS, ch = idx - row * CHUNKS;
-            if ((32 * CHUNKS) % 64 == 0 || idx < 32 * CHUNKS) {
-                const unsigned off8 = rowinfo[2 * row];
-                const unsigned room = rowinfo[2 * row + 1];
-                const int n = n_lo + 8 * ch;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(slab + row * PITCH + ch * 16);
-                if (n < g.NCo && (unsigned)(n + 8) <= room)
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + ((long long)off8 + (n >> 3)));
+        for (int p = 0; p < PASSES; ++p) {
+            const int row = st_row[p];
+            if ((32 * CHUNKS) % 64 == 0 || row < 32) {
+                const unsigned mrow = cur_m0 + (unsigned)row;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(slab + row * PITCH + (st_n8[p] - (n_lo >> 3)) * 16);
+                bool ok = mrow < (unsigned)g.M && st_n8[p] * 8 < g.NCo;
+                unsigned long long off8;
+                if (a.linear_out) {
+                    off8 = (unsigned long long)mrow * (unsigned)(g.NCo >> 3) + (unsigned)st_n8[p];
+                } else {
+                    const unsigned t = cur_wo0 + (unsigned)row;
+                    const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
+                    const unsigned oc = (t - q * (unsigned)g.Wf_out) * (unsigned)g.NCo + (unsigned)st_n8[p] * 8u;
+                    ok = ok && oc + 8u <= (unsigned)g.out_row;
+                    off8 = ((unsigned long long)(cur_rowid0 + q) * (unsigned)g.out_row + oc) >> 3;
+                }
+                if (ok) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
             }
         }
         wave_lds_sync();
     }
 }
 
+static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
+
 template <typename TR, int NT, int KHM, int KSM, int OCC>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y,
                 hipStream_t st) {
     using T = typename TR::T;
     StreamArgs a;
-    a.MT = (g.M + 31) / 32;
+    a.MT = (unsigned)((g.M + 31) / 32);
     a.NG = (g.NCo + 32 * NT - 1) / (32 * NT);
     a.ksteps = ksteps;
-    // Persistent grid: OCC workgroups per CU on 256 CUs, rounded so that the
-    // wave count is a multiple of NG (each M tile is then finished by NG waves
-    // running side by side) and no more tiles in flight than there are tiles.
-    long long waves = 256LL * OCC * 4;
+    // Persistent grid: as many workgroups as stay resident on 256 CUs (asked
+    // of the runtime once per instance), rounded so that the wave count is a
+    // multiple of NG (each M tile is then finished by NG waves running side
+    // by side) and no more tiles in flight than there are tiles.
+    static int resident = 0;  // workgroups per CU; benign race: every thread computes the same value
+    if (resident == 0) {
+        int nb = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
+                &nb, conv_stream_kernel<TR, NT, KHM, KSM, OCC, true, false>, 256, 0) != hipSuccess || nb < 1)
+            nb = OCC;
+        resident = nb > 4 ? 4 : nb;
+    }
+    int per_cu = resident;
+    if (const char *e = getenv("FOLDCONV_TUNE_WGS_PER_CU")) per_cu = atoi(e) > 0 ? atoi(e) : per_cu;
+    long long waves = 256LL * per_cu * 4;
     long long J = waves / a.NG;
     if (J < 1) J = 1;
     if (J > a.MT) J = a.MT;
-    a.J = J;
-    const long long blocks = (J * a.NG + 3) / 4;
-    conv_stream_kernel<TR, NT, KHM, KSM, OCC><<<(unsigned)blocks, 256, 0, st>>>(
-        g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+    a.J = (unsigned)J;
+    const long long S = J * 32, plane = (long long)g.Hout * g.Wf_out;
+    a.dI = (unsigned)(S / plane);
+    a.dH = (unsigned)((S % plane) / g.Wf_out);
+    a.dW = (unsigned)((S % plane) % g.Wf_out);
+    a.mgW = magic_for((unsigned)g.Wf_out);
+    a.mgH = magic_for((unsigned)g.Hout);
+    a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
+    a.linear_out = g.out_row == g.Wf_out * g.NCo ? 1 : 0;
+    const unsigned blocks = (unsigned)((J * a.NG + 3) / 4);
+    const bool exact = g.KH == KHM && ksteps == KSM;
+#define FC_GO(EX, RL)                                                                       \
+    conv_stream_kernel<TR, NT, KHM, KSM, OCC, EX, RL><<<blocks, 256, 0, st>>>(              \
+        g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y)
+    if (exact && g.relu) FC_GO(true, true);
+    else if (exact) FC_GO(true, false);
+    else if (g.relu) FC_GO(false, true);
+    else FC_GO(false, false);
+#undef FC_GO
     return (int)hipGetLastError();
 }
 

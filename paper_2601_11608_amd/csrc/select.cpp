@@ -27,8 +27,16 @@ int max_ksteps(ConvGeom g, int band, int cols) {
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of 8.
     if (g.FC % 8 != 0 || g.NCo % 8 != 0 || g.out_row % 8 != 0 || g.kwin % 8 != 0) return false;
+    // 32-bit element offsets into x, 32-bit (offset / 8) into y.
+    const long long x_elems = (long long)g.N * g.H * g.in_row;
+    const long long y_elems = (long long)g.N * g.Hout * g.out_row;
+    if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems / 8 >= (1LL << 32)) return false;
+    // exact multiply-high division of (tile start + lane) by the folded width and by the output height
+    if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     static const int prefer[] = {4, 2, 1};
+    const char *tune = getenv("FOLDCONV_TUNE_NT");
     for (int nt : prefer) {
+        if (tune && atoi(tune) > 0 && atoi(tune) != nt) continue;
         const int ks = max_ksteps(g, band, 32 * nt);
         for (int i = 0; i < kNumInst; ++i)
             if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
