@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "launch.h"
 #include "mfma_types.h"
 
@@ -46,12 +48,19 @@ __device__ __forceinline__ unsigned pack2<BF16Traits>(float a, float b) {
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
-    // Orders this wave's LDS writes before its later LDS reads of other lanes'
-    // data (LDS executes a wave's instructions in order; this stops the
-    // compiler from moving them and waits for outstanding LDS operations).
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    // A wave's LDS instructions execute in issue order, so data one lane wrote is visible to
+    // the other lanes' later reads without any wait.  All that is needed is to keep the
+    // compiler from moving LDS accesses across this point.
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    asm volatile("" ::: "memory");
+}
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
 }
 
 struct StreamArgs {
@@ -84,6 +93,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     constexpr int SLAB = 32 * PITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * SLAB];
 
+    constexpr unsigned kOutOfRange = 0x80000000u;  // beyond any resource extent used here
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, hf = lane >> 5;
@@ -133,9 +143,21 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     // Input fragments come through a range-checked buffer resource: a lane whose
     // fragment lies outside the image (zero padding) uses an offset beyond the
     // extent and receives zeros, with no branch and no select afterwards.
-    const __amdgpu_buffer_rsrc_t xr =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(x), 0, (int)a.x_bytes, 0x00020000);
-    constexpr unsigned kOutOfRange = 0x80000000u;
+    // The loads are issued from inline assembly and waited for with explicit counts (see the
+    // loop head): the compiler's own wait insertion would make every wave wait for its
+    // previous tile's stores before touching the next tile's input.
+    u32x4 xr;
+    {
+        const unsigned long long xa = (unsigned long long)x;
+        xr[0] = (unsigned)xa;
+        xr[1] = (unsigned)(xa >> 32) & 0xffffu;  // stride 0: raw buffer, byte offsets
+        xr[2] = a.x_bytes;
+        xr[3] = 0x00020000u;
+        xr[0] = __builtin_amdgcn_readfirstlane(xr[0]);
+        xr[1] = __builtin_amdgcn_readfirstlane(xr[1]);
+        xr[2] = __builtin_amdgcn_readfirstlane(xr[2]);
+        xr[3] = __builtin_amdgcn_readfirstlane(xr[3]);
+    }
 
     // ---- the wave's current tile: first pixel m0 = (img0, ho0, wo0), advanced incrementally ----
     unsigned m0 = j0 * 32u;
@@ -152,14 +174,22 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     for (int ks = 0; ks < KSM; ++ks)
         if (ks < KS && e0 + 16 * ks < e_hi) ksmask |= 1u << ks;
 
-    // per-lane constants of the row-wise store phase
-    int st_row[PASSES], st_n8[PASSES];
+    // per-lane constants of the row-wise store phase: LDS byte offset of the lane's 16-byte
+    // chunk in each pass and, when stored rows are contiguous (linear_out), its byte offset
+    // from the tile's first output element
+    int st_row[PASSES], st_col[PASSES], st_lds[PASSES];
+    unsigned st_lin[PASSES];
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int idx = p * 64 + lane;
         st_row[p] = idx / CHUNKS;
-        st_n8[p] = (n_lo >> 3) + (idx - st_row[p] * CHUNKS);
+        const int ch = idx - st_row[p] * CHUNKS;
+        st_col[p] = n_lo + 8 * ch;  // first output column of the chunk
+        const bool in = st_row[p] < 32 && st_col[p] < g.NCo;
+        st_lds[p] = (in ? st_row[p] : 0) * PITCH + ch * 16;
+        st_lin[p] = in ? 2u * ((unsigned)st_row[p] * (unsigned)g.NCo + (unsigned)st_col[p]) : kOutOfRange;
     }
+    const unsigned long long y_rows_total = (unsigned long long)g.N * (unsigned)g.Hout;
 
     u32x4 xf[KHM][KSM];
     auto load_tile = [&](u32x4 (&dst)[KHM][KSM]) {
@@ -189,7 +219,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 // (col and in_row are multiples of 8)
                 const bool ok = rv && ((colok >> ks) & 1u);
                 const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRange;
-                dst[kh][ks] = __builtin_amdgcn_raw_buffer_load_b128(xr, voff, 0, 0);
+                asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst[kh][ks]) : "v"(voff), "s"(xr) : "memory");
             }
         }
     };
@@ -204,7 +234,12 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         img0 += a.dI + c;
     };
 
+    // Nothing the compiler tracks may be in flight when the hand-counted loads start.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     load_tile(xf);
+    // Drain the first tile's loads here: the loop head then only ever waits for loads that were
+    // issued ahead of PASSES stores of the previous tile, and leaves those stores in flight.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     for (unsigned mt = j0; mt < a.MT; mt += a.J) {
         floatx16_t acc[NT];
@@ -213,20 +248,30 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
+        static_for<0, KHM * KSM>([&](auto step) {
+            constexpr int idx = decltype(step)::value;
+            constexpr int kh = idx / KSM, ks = idx % KSM;
+            if (EXACT || (kh < KH && ks < KS)) {
+                // Vector-memory operations retire in issue order.  Behind this fragment's load
+                // the wave has issued the remaining fragment loads of the tile and then exactly
+                // PASSES stores, so the fragment has landed once at most that many operations
+                // are outstanding.  (Guarded-off K-steps only make the count stricter.)
+                // Instances with run-time K guards take the plain full wait instead.
+                constexpr int kBehindAll = EXACT ? (KHM * KSM - 1 - idx) + PASSES : 0;
+                constexpr int kBehind = kBehindAll < 63 ? kBehindAll : 63;
+                asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");
+                const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
 #pragma unroll
-        for (int kh = 0; kh < KHM; ++kh)
-#pragma unroll
-            for (int ks = 0; ks < KSM; ++ks)
-                if (EXACT || (kh < KH && ks < KS)) {
-                    const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
-                }
+                for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
+            }
+        });
 
         // where this tile's rows go (wave-uniform part), then move on and prefetch
         const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_rowid0 = img0 * (unsigned)g.Hout + ho0;
         advance();
-        if (mt + a.J < a.MT) load_tile(xf);  // the next tile's input stays in flight across the epilogue
+        // The next tile's input stays in flight across the epilogue.  Past the last tile every
+        // lane's pixel is >= M, so all offsets are out of range and nothing is fetched.
+        load_tile(xf);
 
         // ---- epilogue: round, ReLU, transpose through LDS, row-contiguous stores ----
 #pragma unroll
@@ -244,24 +289,37 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 *reinterpret_cast<u32x2 *>(slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * 2) = pk;
             }
         wave_lds_sync();
+        // Stores go through a range-checked buffer resource based at the tile's first output
+        // row: lanes that have nothing to store (pixels past the end, cropped columns) use an
+        // out-of-range offset and the hardware drops them.  No branch surrounds a store, so
+        // the input prefetch above is not held back by store completion.
+        {
+            unsigned long long base_el, left_el;  // first element of the resource, elements to the end of y
+            if (a.linear_out) {
+                base_el = (unsigned long long)cur_m0 * (unsigned)g.NCo;
+                left_el = ((unsigned long long)g.M - cur_m0) * (unsigned)g.NCo;
+            } else {
+                base_el = (unsigned long long)cur_rowid0 * (unsigned)g.out_row;
+                left_el = (y_rows_total - cur_rowid0) * (unsigned)g.out_row;
+            }
+            const unsigned long long left_b = left_el * 2ull;
+            const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(
+                y + base_el, 0, (int)(left_b > 0x7fffffffull ? 0x7fffffffull : left_b), 0x00020000);
 #pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int row = st_row[p];
-            if ((32 * CHUNKS) % 64 == 0 || row < 32) {
-                const unsigned mrow = cur_m0 + (unsigned)row;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(slab + row * PITCH + (st_n8[p] - (n_lo >> 3)) * 16);
-                bool ok = mrow < (unsigned)g.M && st_n8[p] * 8 < g.NCo;
-                unsigned long long off8;
+            for (int p = 0; p < PASSES; ++p) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(slab + st_lds[p]);
+                unsigned off;
                 if (a.linear_out) {
-                    off8 = (unsigned long long)mrow * (unsigned)(g.NCo >> 3) + (unsigned)st_n8[p];
+                    off = st_lin[p];
                 } else {
-                    const unsigned t = cur_wo0 + (unsigned)row;
+                    const unsigned t = cur_wo0 + (unsigned)st_row[p];
                     const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
-                    const unsigned oc = (t - q * (unsigned)g.Wf_out) * (unsigned)g.NCo + (unsigned)st_n8[p] * 8u;
-                    ok = ok && oc + 8u <= (unsigned)g.out_row;
-                    off8 = ((unsigned long long)(cur_rowid0 + q) * (unsigned)g.out_row + oc) >> 3;
+                    const unsigned oc = (t - q * (unsigned)g.Wf_out) * (unsigned)g.NCo + (unsigned)st_col[p];
+                    const bool ok = st_lin[p] != kOutOfRange && cur_m0 + (unsigned)st_row[p] < (unsigned)g.M &&
+                                    oc + 8u <= (unsigned)g.out_row;
+                    off = ok ? 2u * (q * (unsigned)g.out_row + oc) : kOutOfRange;
                 }
-                if (ok) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
+                __builtin_amdgcn_raw_buffer_store_b128(v, yr, off, 0, 2 /* nt */);
             }
         }
         wave_lds_sync();

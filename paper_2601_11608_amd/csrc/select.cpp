@@ -33,6 +33,8 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems / 8 >= (1LL << 32)) return false;
     // exact multiply-high division of (tile start + lane) by the folded width and by the output height
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
+    // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
+    if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
     static const int prefer[] = {4, 2, 1};
     const char *tune = getenv("FOLDCONV_TUNE_NT");
     for (int nt : prefer) {
