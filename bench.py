@@ -28,24 +28,24 @@ MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 
 
 def time_events(fn, steps, warmup):
-    """Runs fn warmup+steps times; returns (wall ms/step, mean device ms per call) for the timed steps."""
+    """Runs fn warmup+steps times.  Returns (wall ms/step, device ms/step): wall clock between
+    two synchronisations around exactly `steps` calls, and HIP-event time over the same region
+    on the stream the kernels are launched on, both divided by `steps`."""
     import torch
 
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    for i in range(steps):
-        starts[i].record()
+    e0.record()
+    for _ in range(steps):
         fn()
-        ends[i].record()
+    e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    dev = sorted(s.elapsed_time(e) for s, e in zip(starts, ends))
-    return wall_ms, sum(dev) / len(dev), dev[len(dev) // 2], dev[0]
+    return wall_ms, e0.elapsed_time(e1) / steps
 
 
 def cpu_baseline(layer, x, w, b):
@@ -96,7 +96,7 @@ def main():
     def step():
         L.forward(xd, y)
 
-    wall_ms, dev_ms, dev_med, dev_min = time_events(step, args.steps, args.warmup)
+    wall_ms, dev_ms = time_events(step, args.steps, args.warmup)
     useful_tflops = s.useful_flops / (wall_ms * 1e-3) / 1e12
     algo_bytes = s.x_bytes + s.w_exp_bytes + s.bias_bytes + s.y_bytes  # x + packed w' + b read once, y written once
     achieved_gbs = algo_bytes / (dev_ms * 1e-3) / 1e9
@@ -137,7 +137,7 @@ def main():
         def step_dense():
             L.forward(xd, y, flags=fc.FLAG_DENSE_K)
 
-        _, d_ms, _, _ = time_events(step_dense, max(3, args.steps // 5), 2)
+        _, d_ms = time_events(step_dense, max(3, args.steps // 5), 2)
         extras["dense_k"] = {
             "kernel_ms": d_ms,
             "useful_tflops": s.useful_flops / (d_ms * 1e-3) / 1e12,
@@ -148,7 +148,7 @@ def main():
         def step_padded():
             L.forward_padded(xd, y)
 
-        _, p_ms, _, _ = time_events(step_padded, max(3, args.steps // 5), 2)
+        _, p_ms = time_events(step_padded, max(3, args.steps // 5), 2)
         extras["padded"] = {
             "ms": p_ms,
             "C_pad": s.C_pad,
@@ -159,7 +159,7 @@ def main():
         def step_repack():
             L.forward(xd, y, repack=True)
 
-        _, r_ms, _, _ = time_events(step_repack, max(3, args.steps // 5), 2)
+        _, r_ms = time_events(step_repack, max(3, args.steps // 5), 2)
         extras["with_filter_repack_ms"] = r_ms
         # materialised fold and reconstruct copies (not on the timed path: both alias)
         nbuf = 8
@@ -171,7 +171,7 @@ def main():
             fc.foldconv_fold_input(L.plan, xs_src[k[0] % nbuf], xs_rot[k[0] % nbuf])
             k[0] += 1
 
-        _, f_ms, _, _ = time_events(step_fold, 40, 8)
+        _, f_ms = time_events(step_fold, 40, 8)
         extras["fold_copy"] = {"ms": f_ms, "GBps": 2 * s.x_bytes / (f_ms * 1e-3) / 1e9,
                                "frac_of_hbm_peak": 2 * s.x_bytes / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                "note": "rotating %d buffer pairs (%.0f MB) to defeat the 256 MB cache" % (nbuf, 2 * nbuf * s.x_bytes / 1e6)}
@@ -180,7 +180,7 @@ def main():
         def step_unfold():
             fc.foldconv_unfold_output(L.plan, y, y2)
 
-        _, u_ms, _, _ = time_events(step_unfold, 10, 2)
+        _, u_ms = time_events(step_unfold, 10, 2)
         extras["unfold_copy"] = {"ms": u_ms, "GBps": 2 * s.y_bytes / (u_ms * 1e-3) / 1e9,
                                  "frac_of_hbm_peak": 2 * s.y_bytes / (u_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del xs_rot, xs_src, y2
