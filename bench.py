@@ -24,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the folded convolution on the headline layer from rocprofv3 counters
+# (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 1.000 + FETCH_SIZE x 1.997).  Set to None whenever
+# the convolution kernel changes after the counters were taken.
+MEASURED_TRAFFIC_BYTES = 431.9e6
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 
 
@@ -123,7 +127,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES,
             "kernel_ms": dev_ms,
             "algorithmic_bytes": algo_bytes,
         },

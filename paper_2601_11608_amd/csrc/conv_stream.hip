@@ -20,8 +20,6 @@
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "launch.h"
@@ -65,7 +63,9 @@ __device__ __forceinline__ void static_for(F &&f) {
 
 struct StreamArgs {
     unsigned MT;        // number of 32-pixel M tiles
-    unsigned J;         // M tiles in flight = stride of a wave's M-tile walk
+    unsigned J;         // M tiles in flight per partition = stride of a wave's M-tile walk
+    unsigned parts;     // 1, or 8: one contiguous range of M tiles per XCD (workgroup b runs on XCD b % 8)
+    unsigned TPP;       // M tiles per partition
     int NG;             // column groups of NT*32 columns
     int ksteps;         // 16-wide K-steps per kh actually walked (<= KSM)
     unsigned dW, dH, dI;  // the walk stride of 32*J pixels as (folded column, row, image) steps
@@ -99,10 +99,15 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     const int r = lane & 31, hf = lane >> 5;
     unsigned char *slab = lds_all + wave * SLAB;
 
-    const unsigned gw = blockIdx.x * 4 + wave;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Giving every XCD
+    // one contiguous range of M tiles keeps each input row in a single L2 instead of all eight.
+    const unsigned part = blockIdx.x % a.parts;
+    const unsigned gw = (blockIdx.x / a.parts) * 4 + wave;
     const int ng = (int)(gw % (unsigned)a.NG);
     const unsigned j0 = gw / (unsigned)a.NG;
     if (j0 >= a.J) return;  // wave-uniform
+    const unsigned t_first = part * a.TPP;                                     // first tile of the partition
+    const unsigned t_end = t_first + a.TPP < a.MT ? t_first + a.TPP : a.MT;    // one past its last tile
 
     const int KH = EXACT ? KHM : g.KH;
     const int KS = EXACT ? KSM : a.ksteps;
@@ -160,7 +165,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     }
 
     // ---- the wave's current tile: first pixel m0 = (img0, ho0, wo0), advanced incrementally ----
-    unsigned m0 = j0 * 32u;
+    unsigned m0 = (t_first + j0) * 32u;
     unsigned wo0 = m0 % (unsigned)g.Wf_out;
     unsigned ho0, img0;
     {
@@ -241,7 +246,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     // issued ahead of PASSES stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    for (unsigned mt = j0; mt < a.MT; mt += a.J) {
+    for (unsigned mt = t_first + j0; mt < t_end; mt += a.J) {
         floatx16_t acc[NT];
         floatx16_t zero;
 #pragma unroll
@@ -269,8 +274,9 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         // where this tile's rows go (wave-uniform part), then move on and prefetch
         const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_rowid0 = img0 * (unsigned)g.Hout + ho0;
         advance();
-        // The next tile's input stays in flight across the epilogue.  Past the last tile every
-        // lane's pixel is >= M, so all offsets are out of range and nothing is fetched.
+        // The next tile's input stays in flight across the epilogue.  After the wave's last tile
+        // this fetches a tile that is never used: lanes past the end of the image get zeros from
+        // the range check, the others read valid input, so the load is always safe.
         load_tile(xf);
 
         // ---- epilogue: round, ReLU, transpose through LDS, row-contiguous stores ----
@@ -346,14 +352,15 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
                 &nb, conv_stream_kernel<TR, NT, KHM, KSM, OCC, true, false>, 256, 0) != hipSuccess || nb < 1)
             nb = OCC;
-        resident = nb > 4 ? 4 : nb;
+        resident = nb > 2 ? 2 : nb;
     }
-    int per_cu = resident;
-    if (const char *e = getenv("FOLDCONV_TUNE_WGS_PER_CU")) per_cu = atoi(e) > 0 ? atoi(e) : per_cu;
-    long long waves = 256LL * per_cu * 4;
+    const int per_cu = resident;
+    a.parts = a.MT >= 64 * 8 ? 8 : 1;  // one tile range per XCD unless there are too few tiles to split
+    a.TPP = (a.MT + a.parts - 1) / a.parts;
+    long long waves = 256LL * per_cu * 4 / a.parts;  // per partition
     long long J = waves / a.NG;
     if (J < 1) J = 1;
-    if (J > a.MT) J = a.MT;
+    if (J > a.TPP) J = a.TPP;
     a.J = (unsigned)J;
     const long long S = J * 32, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
@@ -363,7 +370,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.mgH = magic_for((unsigned)g.Hout);
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.linear_out = g.out_row == g.Wf_out * g.NCo ? 1 : 0;
-    const unsigned blocks = (unsigned)((J * a.NG + 3) / 4);
+    const unsigned blocks = (unsigned)((J * a.NG + 3) / 4) * a.parts;
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                       \
     conv_stream_kernel<TR, NT, KHM, KSM, OCC, EX, RL><<<blocks, 256, 0, st>>>(              \

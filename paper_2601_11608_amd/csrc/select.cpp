@@ -1,7 +1,5 @@
 // Which convolution kernel serves a geometry, and the tiling facts the plan
 // needs for FLOP accounting.  Host only.
-#include <stdlib.h>
-
 #include "launch.h"
 
 namespace {
@@ -35,10 +33,10 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
     if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
-    static const int prefer[] = {4, 2, 1};
-    const char *tune = getenv("FOLDCONV_TUNE_NT");
+    // 64 columns per wave first: for the small-C_in layers this is one K-step per kh with the
+    // fewest structural-zero products; wider or narrower waves only when no such instance fits.
+    static const int prefer[] = {2, 4, 1};
     for (int nt : prefer) {
-        if (tune && atoi(tune) > 0 && atoi(tune) != nt) continue;
         const int ks = max_ksteps(g, band, 32 * nt);
         for (int i = 0; i < kNumInst; ++i)
             if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
