@@ -188,6 +188,16 @@ def main():
         extras["unfold_copy"] = {"ms": u_ms, "GBps": 2 * s.y_bytes / (u_ms * 1e-3) / 1e9,
                                  "frac_of_hbm_peak": 2 * s.y_bytes / (u_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del xs_rot, xs_src, y2
+        # the 5-layer bf16 stack (3->20->36->68->132->256, 112x112, N=32), folded vs zero-padded
+        l5, x5, w5, b5 = wl.make_config("c5")
+        stack = runner.FoldedStack(l5, w5, b5)
+        x5d = x5.cuda()
+        flops5 = sum(L5.plan.shapes.useful_flops for L5 in stack.layers)
+        _, s_ms = time_events(lambda: stack.forward(x5d), 10, 2)
+        _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 10, 2)
+        extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,
+                              "useful_pct_of_mfma_peak": 100.0 * flops5 / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+                              "kernels": [["gather", "tiled", "stream"][L5.plan.shapes.conv_kernel] for L5 in stack.layers]}
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

@@ -5,11 +5,14 @@ int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const voi
                    const void *w_pack, const void *bias, void *y, void *stream) {
     switch (kernel) {
         case FC_KERNEL_STREAM: {
-            // The dense walk may need more K-steps than any streaming instance holds.
+            // The dense walk may need more K-steps than any streaming instance holds;
+            // the tiled kernel reads the same packed filter.
             StreamShape sh;
             if (fc_stream_shape(g, g.band, &sh)) return fc_launch_conv_stream(dt, g, x, w_pack, bias, y, stream);
-            return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);
+            return fc_launch_conv_tiled(dt, g, x, w_pack, bias, y, stream);
         }
+        case FC_KERNEL_TILED:
+            return fc_launch_conv_tiled(dt, g, x, w_pack, bias, y, stream);
         case FC_KERNEL_GATHER:
         default:
             return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);

@@ -1,0 +1,267 @@
+// LDS-tiled MFMA convolution for layers whose K extent is too large for the
+// filter-stationary streaming kernel (tens to hundreds of 16-wide K-steps):
+// there the matrix cores, not HBM, bound the layer.
+//
+// One 256-thread workgroup (4 waves, 2 x 2) computes a 128 (output columns n)
+// x 128 (folded output pixels m) tile of y'^T; each wave a 64 x 64 quadrant as
+// 2 x 2 MFMA tiles of 32 x 32.  K = (kh, extended channel e) is walked in
+// blocks of 32 elements (two MFMA K-steps), restricted to the band of w' that
+// can be non-zero for the tile's output slots (paper: Eq. "filter_construct";
+// off-band blocks are structural zeros) unless the dense walk is asked for.
+// Both operands are staged through LDS in MFMA operand order, one 16-byte
+// chunk (8 consecutive K values of one row/column) per lane access:
+//   filter: pack[kh][q][n][8] rows copied as they are (coalesced),
+//   input:  the window chunk [e, e+8) of each pixel's input row, a 16-byte
+//           range-checked buffer load (zero padding = out-of-range offset).
+// Global loads for block i+1 are issued before the MFMAs of block i and
+// written to the other LDS stage afterwards: one barrier per K block.
+// Epilogue: bias as a rank-1 MFMA, ReLU, one rounding, transpose through LDS,
+// 16-byte row-contiguous stores with the reconstruct step fused in.
+// paper: Eq. "new_conv_H", Eq. "bias_construct", Reconstruct step.
+#include <hip/hip_runtime.h>
+
+#include "launch.h"
+#include "mfma_types.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BN = 128, BM = 128, BK = 32;
+constexpr int QPB = BK / 8;                 // 16-byte chunks per row per K block
+constexpr int PLANE = BN * 16 + 16;         // bytes of one chunk plane (padded against bank conflicts)
+constexpr int STAGE = 2 * QPB * PLANE;      // filter planes then input planes
+constexpr int EPITCH = BN * 2 + 16;         // bytes per row of the transposed output tile
+constexpr int LDS_BYTES = (2 * STAGE > BM * EPITCH) ? 2 * STAGE : BM * EPITCH;
+constexpr unsigned kOutOfRange = 0x80000000u;
+
+template <typename TR>
+__device__ __forceinline__ unsigned pack2t(float a, float b);
+template <>
+__device__ __forceinline__ unsigned pack2t<F16Traits>(float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(unsigned, v);
+}
+template <>
+__device__ __forceinline__ unsigned pack2t<BF16Traits>(float a, float b) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    b2 v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(unsigned, v);
+}
+
+struct TiledArgs {
+    unsigned tiles_n, tiles_m;
+    unsigned total;      // tiles_n * tiles_m
+    unsigned per_xcd;    // ceil(total / 8)
+    unsigned x_bytes, wp_bytes;
+};
+
+template <typename TR, bool RELU>
+__global__ void __launch_bounds__(256, 2)
+conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
+                  const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
+    using T = typename TR::T;
+    using Vec = typename TR::Vec;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+
+    // Workgroup b runs on XCD b % 8.  Each XCD takes one contiguous range of tiles, N tiles
+    // fastest, so the tiles that share an input window meet in one L2.
+    const unsigned tile = (blockIdx.x % 8u) * a.per_xcd + blockIdx.x / 8u;
+    if (blockIdx.x / 8u >= a.per_xcd || tile >= a.total) return;  // uniform per workgroup
+    const unsigned tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
+    const int n0 = (int)tn * BN;
+    const unsigned m0 = tm * BM;
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int r = lane & 31, hf = lane >> 5;
+    const int wn = wave & 1, wm = wave >> 1;
+
+    int e_lo, e_hi;
+    fc_band_window(g, n0, n0 + BN, 8, &e_lo, &e_hi);
+    const int kblocks = (e_hi - e_lo + BK - 1) / BK;  // per kh
+    const int T_total = g.KH * kblocks;
+    const int q_per_kh = g.kwin / 8;
+
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(x), 0, (int)a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(wp), 0, (int)a.wp_bytes, 0x00020000);
+
+    // ---- this thread's share of the staging loads -----------------------------
+    // input: chunk column qi of pixels mi[0], mi[1]; filter: chunk planes qf[0], qf[1] of column nf
+    const int qi = t & 3;
+    int pix[2], ho_[2], col_[2];
+    bool vm[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const unsigned m = m0 + (unsigned)(t >> 2) + 64u * i;
+        vm[i] = m < (unsigned)g.M;
+        const unsigned mm = vm[i] ? m : 0u;
+        const unsigned wo = mm % (unsigned)g.Wf_out;
+        const unsigned rowid = mm / (unsigned)g.Wf_out;
+        const unsigned ho = rowid % (unsigned)g.Hout;
+        const unsigned img = rowid / (unsigned)g.Hout;
+        ho_[i] = (int)ho;
+        col_[i] = (int)wo * g.FC + 8 * qi;
+        pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
+    }
+    const int nf = t & 127;
+    const int qf0 = t >> 7;  // 0 or 1; second chunk is plane qf0 + 2
+    const bool vn = n0 + nf < g.NCo;
+
+    u32x4 ri[2], rf[2];
+    auto load_block = [&](int kh, int e0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int hi = ho_[i] + kh - g.pad_h;
+            const int e = e0 + 8 * qi;
+            const int col = col_[i] + e0;
+            const bool ok = vm[i] && hi >= 0 && hi < g.H && e < e_hi && col >= 0 && col < g.in_row;
+            const unsigned off = ok ? 2u * (unsigned)(pix[i] + kh * g.in_row + e0) : kOutOfRange;
+            ri[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int e = e0 + 8 * (qf0 + 2 * i);
+            const bool ok = vn && e < e_hi;
+            const unsigned row = (unsigned)(kh * q_per_kh + ((e - g.e_min) >> 3));
+            const unsigned off = ok ? 16u * (row * (unsigned)g.NCo + (unsigned)(n0 + nf)) : kOutOfRange;
+            rf[i] = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
+        }
+    };
+    auto store_block = [&](int stage) {
+        unsigned char *sf = lds + stage * STAGE;
+        unsigned char *si = sf + QPB * PLANE;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<u32x4 *>(si + qi * PLANE + ((t >> 2) + 64 * i) * 16) = ri[i];
+            *reinterpret_cast<u32x4 *>(sf + (qf0 + 2 * i) * PLANE + nf * 16) = rf[i];
+        }
+    };
+
+    // ---- accumulators, initialised with the bias through a rank-1 MFMA ----------
+    floatx16_t acc[2][2];
+    {
+        Vec ones;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ones[i] = (T)0.0f;
+        if (hf == 0) ones[0] = (T)1.0f;
+        floatx16_t zero;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            Vec bf;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) bf[i] = (T)0.0f;
+            const int n = n0 + wn * 64 + nt * 32 + r;
+            if (g.has_bias && hf == 0 && n < g.NCo) bf[0] = bias[n % g.Co];
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = TR::mfma(bf, ones, zero);
+        }
+    }
+
+    // ---- K loop -----------------------------------------------------------------
+    int kh = 0, kb = 0;  // block being computed
+    if (T_total > 0) {
+        load_block(0, e_lo);
+        store_block(0);
+    }
+    __syncthreads();
+    for (int it = 0; it < T_total; ++it) {
+        int kh_n = kh, kb_n = kb + 1;
+        if (kb_n == kblocks) { kb_n = 0; ++kh_n; }
+        const bool more = it + 1 < T_total;
+        if (more) load_block(kh_n, e_lo + kb_n * BK);
+
+        const unsigned char *sf = lds + (it & 1) * STAGE;
+        const unsigned char *si = sf + QPB * PLANE;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int qc = 2 * s + hf;
+            Vec af[2], bfv[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+                af[nt] = *reinterpret_cast<const Vec *>(sf + qc * PLANE + (wn * 64 + nt * 32 + r) * 16);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                bfv[mt] = *reinterpret_cast<const Vec *>(si + qc * PLANE + (wm * 64 + mt * 32 + r) * 16);
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = TR::mfma(af[nt], bfv[mt], acc[nt][mt]);
+        }
+        if (more) store_block((it + 1) & 1);
+        __syncthreads();
+        kh = kh_n;
+        kb = kb_n;
+    }
+
+    // ---- epilogue: round, ReLU, transpose through LDS (stages are free after the last barrier) ----
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32x2 pk = {pack2t<TR>(acc[nt][mt][4 * q], acc[nt][mt][4 * q + 1]),
+                            pack2t<TR>(acc[nt][mt][4 * q + 2], acc[nt][mt][4 * q + 3])};
+                if (RELU) {
+                    typedef short s16x4 __attribute__((ext_vector_type(4)));
+                    const s16x4 z = {0, 0, 0, 0};
+                    pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
+                }
+                const int row = wm * 64 + mt * 32 + r;
+                const int col = wn * 64 + nt * 32 + 8 * q + 4 * hf;
+                *reinterpret_cast<u32x2 *>(lds + row * EPITCH + col * 2) = pk;
+            }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < (BM * BN / 8) / 256; ++i) {
+        const int idx = i * 256 + t;
+        const int row = idx >> 4, ch = idx & 15;
+        const unsigned m = m0 + (unsigned)row;
+        const int n = n0 + 8 * ch;
+        if (m < (unsigned)g.M && n < g.NCo) {
+            const unsigned wo = m % (unsigned)g.Wf_out;
+            const unsigned rowid = m / (unsigned)g.Wf_out;
+            const unsigned oc = wo * (unsigned)g.NCo + (unsigned)n;
+            if (oc + 8u <= (unsigned)g.out_row) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * EPITCH + ch * 16);
+                const unsigned long long off8 = ((unsigned long long)rowid * (unsigned)g.out_row + oc) >> 3;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
+            }
+        }
+    }
+}
+
+template <typename TR>
+int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
+    using T = typename TR::T;
+    TiledArgs a;
+    a.tiles_n = (unsigned)((g.NCo + BN - 1) / BN);
+    a.tiles_m = (unsigned)((g.M + BM - 1) / BM);
+    const unsigned long long total = (unsigned long long)a.tiles_n * a.tiles_m;
+    if (total > 0x7fffff00ull) return (int)hipErrorInvalidValue;
+    a.total = (unsigned)total;
+    a.per_xcd = (a.total + 7) / 8;
+    a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
+    a.wp_bytes = (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
+    const unsigned blocks = a.per_xcd * 8;
+    if (g.relu)
+        conv_tiled_kernel<TR, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+    else
+        conv_tiled_kernel<TR, false><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+    return (int)hipGetLastError();
+}
+
+}  // namespace
+
+int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
+                         void *y, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == FOLDCONV_F16) return launch<F16Traits>(g, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16) return launch<BF16Traits>(g, x, w_pack, bias, y, st);
+    return (int)hipErrorInvalidValue;
+}

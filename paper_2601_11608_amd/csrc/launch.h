@@ -35,5 +35,8 @@ int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const voi
 // Per-kernel launchers behind fc_launch_conv.
 int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
                           void *y, void *stream);
+int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
+                         void *y, void *stream);
+bool fc_tiled_ok(const ConvGeom &g);
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,
                           void *y, void *stream);

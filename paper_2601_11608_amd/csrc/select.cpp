@@ -22,13 +22,22 @@ int max_ksteps(ConvGeom g, int band, int cols) {
 }
 }  // namespace
 
-bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
+// Conditions shared by the two vector kernels.
+static bool vector_ok(const ConvGeom &g) {
     // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of 8.
     if (g.FC % 8 != 0 || g.NCo % 8 != 0 || g.out_row % 8 != 0 || g.kwin % 8 != 0) return false;
-    // 32-bit element offsets into x, 32-bit (offset / 8) into y.
+    // 32-bit byte offsets into x and into the packed filter, 32-bit (offset / 8) into y.
     const long long x_elems = (long long)g.N * g.H * g.in_row;
     const long long y_elems = (long long)g.N * g.Hout * g.out_row;
-    if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems / 8 >= (1LL << 32)) return false;
+    const long long w_elems = (long long)g.KH * g.kwin * g.NCo;
+    if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems / 8 >= (1LL << 32) || w_elems >= (1LL << 30)) return false;
+    return true;
+}
+
+bool fc_tiled_ok(const ConvGeom &g) { return vector_ok(g); }
+
+bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
+    if (!vector_ok(g)) return false;
     // exact multiply-high division of (tile start + lane) by the folded width and by the output height
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
@@ -56,6 +65,7 @@ int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt) {
     if (dt == FOLDCONV_F32) return FC_KERNEL_GATHER;
     StreamShape sh;
     if (fc_stream_shape(g, 1, &sh)) return FC_KERNEL_STREAM;
+    if (fc_tiled_ok(g)) return FC_KERNEL_TILED;
     return FC_KERNEL_GATHER;
 }
 

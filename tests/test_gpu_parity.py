@@ -78,6 +78,9 @@ SMALL = [
     (1, 6, 8, 36, 68, 3, 3, 1, 4, False, False),    # FC=144, NCo=272
     (1, 3, 64, 1, 8, 1, 3, 1, 64, True, False),     # F == W
     (1, 4, 16, 5, 7, 1, 1, 0, 8, True, False),      # 1x1 (GEMM as conv), FC=40
+    (1, 5, 8, 68, 132, 3, 3, 1, 4, True, True),     # FC=272, NCo=528: K too large for the streaming kernel
+    (2, 3, 8, 132, 40, 3, 3, 1, 4, False, False),   # FC=528, NCo=160: ragged N tile of the tiled kernel
+    (1, 20, 28, 68, 32, 3, 3, 1, 4, True, True),    # several 128-pixel M tiles, ragged last one
 ]
 
 
