@@ -30,7 +30,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BN = 128, BM = 128, BK = 32;
 constexpr int QPB = BK / 8;                 // 16-byte chunks per row per K block
-constexpr int PLANE = BN * 16 + 16;         // bytes of one chunk plane (padded against bank conflicts)
+constexpr int PLANE = BN * 16 + 256 / QPB;  // bytes of one chunk plane; the pad staggers the planes so that the 16 lanes
+                                            // of a staging write (QPB chunks x 16/QPB pixels) fall on 16 distinct bank groups
 constexpr int STAGE = 2 * QPB * PLANE;      // filter planes then input planes
 constexpr int EPITCH = BN * 2 + 16;         // bytes per row of the transposed output tile
 constexpr int LDS_BYTES = (2 * STAGE > BM * EPITCH) ? 2 * STAGE : BM * EPITCH;
@@ -90,12 +91,15 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
 
     // ---- this thread's share of the staging loads -----------------------------
     // input: chunk column qi of pixels mi[0], mi[1]; filter: chunk planes qf[0], qf[1] of column nf
-    const int qi = t & 3;
-    int pix[2], ho_[2], col_[2];
-    bool vm[2];
+    constexpr int NI = (BM * QPB) / 256;   // input chunks per thread per K block
+    constexpr int NF = (BN * QPB) / 256;   // filter chunks per thread per K block
+    constexpr int MSTEP = 256 / QPB;       // pixels covered by one pass of the 256 threads
+    const int qi = t & (QPB - 1);
+    int pix[NI], ho_[NI], col_[NI];
+    bool vm[NI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const unsigned m = m0 + (unsigned)(t >> 2) + 64u * i;
+    for (int i = 0; i < NI; ++i) {
+        const unsigned m = m0 + (unsigned)(t / QPB) + (unsigned)(MSTEP * i);
         vm[i] = m < (unsigned)g.M;
         const unsigned mm = vm[i] ? m : 0u;
         const unsigned wo = mm % (unsigned)g.Wf_out;
@@ -106,14 +110,14 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         col_[i] = (int)wo * g.FC + 8 * qi;
         pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
     }
-    const int nf = t & 127;
-    const int qf0 = t >> 7;  // 0 or 1; second chunk is plane qf0 + 2
+    const int nf = t & (BN - 1);
+    const int qf0 = t / BN;  // 0 or 1; chunk i of this thread is plane qf0 + 2*i
     const bool vn = n0 + nf < g.NCo;
 
-    u32x4 ri[2], rf[2];
+    u32x4 ri[NI], rf[NF];
     auto load_block = [&](int kh, int e0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int hi = ho_[i] + kh - g.pad_h;
             const int e = e0 + 8 * qi;
             const int col = col_[i] + e0;
@@ -122,7 +126,7 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
             ri[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NF; ++i) {
             const int e = e0 + 8 * (qf0 + 2 * i);
             const bool ok = vn && e < e_hi;
             const unsigned row = (unsigned)(kh * q_per_kh + ((e - g.e_min) >> 3));
@@ -134,10 +138,11 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         unsigned char *sf = lds + stage * STAGE;
         unsigned char *si = sf + QPB * PLANE;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<u32x4 *>(si + qi * PLANE + ((t >> 2) + 64 * i) * 16) = ri[i];
+        for (int i = 0; i < NI; ++i)
+            *reinterpret_cast<u32x4 *>(si + qi * PLANE + (t / QPB + MSTEP * i) * 16) = ri[i];
+#pragma unroll
+        for (int i = 0; i < NF; ++i)
             *reinterpret_cast<u32x4 *>(sf + (qf0 + 2 * i) * PLANE + nf * 16) = rf[i];
-        }
     };
 
     // ---- accumulators, initialised with the bias through a rank-1 MFMA ----------
@@ -178,7 +183,7 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         const unsigned char *sf = lds + (it & 1) * STAGE;
         const unsigned char *si = sf + QPB * PLANE;
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int s = 0; s < BK / 16; ++s) {
             const int qc = 2 * s + hf;
             Vec af[2], bfv[2];
 #pragma unroll

@@ -19,7 +19,7 @@ struct StreamShape {
 // Filter fragments cost 4*NT*KH*ksteps registers per lane, which bounds the list.
 #define FC_STREAM_INSTANCES(X) \
     X(2, 1, 1, 2) X(2, 3, 1, 2) X(2, 5, 1, 2) X(2, 1, 2, 2) X(2, 3, 2, 2) X(2, 3, 4, 2) X(2, 1, 6, 2) X(2, 3, 9, 1) \
-    X(4, 1, 2, 2) X(4, 3, 2, 2) X(1, 3, 12, 1)
+    X(4, 1, 2, 2) X(4, 3, 2, 2)
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 
 // --- launchers (return 0 or a hipError_t value) -------------------------------

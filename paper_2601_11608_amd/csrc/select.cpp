@@ -43,10 +43,14 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
     if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
     // 64 columns per wave first: for the small-C_in layers this is one K-step per kh with the
-    // fewest structural-zero products; wider or narrower waves only when no such instance fits.
-    static const int prefer[] = {2, 4, 1};
+    // fewest structural-zero products; wider waves only when no such instance fits.
+    static const int prefer[] = {2, 4};
     for (int nt : prefer) {
         const int ks = max_ksteps(g, band, 32 * nt);
+        // Beyond a dozen K-steps per tile the layer is bound by the matrix cores, not by the
+        // output stream, and the LDS-tiled kernel (operands shared by four waves) is the better
+        // tool.  The dense walk of a small-K layer may still use the largest instance.
+        if (band && g.KH * ks > 12) continue;
         for (int i = 0; i < kNumInst; ++i)
             if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
                 out->inst = i;
