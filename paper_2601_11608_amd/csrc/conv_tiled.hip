@@ -2,9 +2,11 @@
 // filter-stationary streaming kernel (tens to hundreds of 16-wide K-steps):
 // there the matrix cores, not HBM, bound the layer.
 //
-// One 256-thread workgroup (4 waves, 2 x 2) computes a 128 (output columns n)
-// x 128 (folded output pixels m) tile of y'^T; each wave a 64 x 64 quadrant as
-// 2 x 2 MFMA tiles of 32 x 32.  K = (kh, extended channel e) is walked in
+// One 256-thread workgroup (4 waves, 2 x 2) computes a BN (output columns n)
+// x 128 (folded output pixels m) tile of y'^T, BN = 128 or 256; each wave a
+// (BN/2) x 64 quadrant as TN x 2 MFMA tiles of 32 x 32 (TN = 2 or 4: the wider
+// tile halves the LDS reads and the input re-reads per MFMA and is used when
+// there are enough output columns to fill it).  K = (kh, extended channel e) is walked in
 // blocks of 32 elements (two MFMA K-steps), restricted to the band of w' that
 // can be non-zero for the tile's output slots (paper: Eq. "filter_construct";
 // off-band blocks are structural zeros) unless the dense walk is asked for.
@@ -28,14 +30,22 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BN = 128, BM = 128, BK = 32;
+constexpr int BM = 128, BK = 32;
 constexpr int QPB = BK / 8;                 // 16-byte chunks per row per K block
-constexpr int PLANE = BN * 16 + 256 / QPB;  // bytes of one chunk plane; the pad staggers the planes so that the 16 lanes
-                                            // of a staging write (QPB chunks x 16/QPB pixels) fall on 16 distinct bank groups
-constexpr int STAGE = 2 * QPB * PLANE;      // filter planes then input planes
-constexpr int EPITCH = BN * 2 + 16;         // bytes per row of the transposed output tile
-constexpr int LDS_BYTES = (2 * STAGE > BM * EPITCH) ? 2 * STAGE : BM * EPITCH;
 constexpr unsigned kOutOfRange = 0x80000000u;
+
+// LDS geometry for a tile of BN output columns
+template <int BN>
+struct TileLds {
+    // bytes of one chunk plane; the pad staggers the planes so that the 16 lanes of a staging write
+    // (QPB chunks x 16/QPB pixels) fall on 16 distinct bank groups
+    static constexpr int PLANE_F = BN * 16 + 256 / QPB;
+    static constexpr int PLANE_I = BM * 16 + 256 / QPB;
+    static constexpr int STAGE = QPB * (PLANE_F + PLANE_I);  // filter planes then input planes
+    static constexpr int EPITCH = BN * 2 + 16;               // bytes per row of the transposed output half-tile
+    static constexpr int EBYTES = 64 * EPITCH;               // the epilogue handles 64 pixels at a time
+    static constexpr int BYTES = (2 * STAGE > EBYTES) ? 2 * STAGE : EBYTES;
+};
 
 template <typename TR>
 __device__ __forceinline__ unsigned pack2t(float a, float b);
@@ -59,13 +69,16 @@ struct TiledArgs {
     unsigned x_bytes, wp_bytes;
 };
 
-template <typename TR, bool RELU>
+template <typename TR, int TN, bool RELU>
 __global__ void __launch_bounds__(256, 2)
 conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                   const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
     using T = typename TR::T;
     using Vec = typename TR::Vec;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+    constexpr int BN = 64 * TN;
+    using L = TileLds<BN>;
+    constexpr int PLANE_F = L::PLANE_F, PLANE_I = L::PLANE_I, STAGE = L::STAGE, EPITCH = L::EPITCH;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[L::BYTES];
 
     // Workgroup b runs on XCD b % 8.  Each XCD takes one contiguous range of tiles, N tiles
     // fastest, so the tiles that share an input window meet in one L2.
@@ -90,7 +103,7 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(wp), 0, (int)a.wp_bytes, 0x00020000);
 
     // ---- this thread's share of the staging loads -----------------------------
-    // input: chunk column qi of pixels mi[0], mi[1]; filter: chunk planes qf[0], qf[1] of column nf
+    // input: chunk column qi of NI pixels, one 16-byte chunk each
     constexpr int NI = (BM * QPB) / 256;   // input chunks per thread per K block
     constexpr int NF = (BN * QPB) / 256;   // filter chunks per thread per K block
     constexpr int MSTEP = 256 / QPB;       // pixels covered by one pass of the 256 threads
@@ -110,12 +123,31 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         col_[i] = (int)wo * g.FC + 8 * qi;
         pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
     }
-    const int nf = t & (BN - 1);
-    const int qf0 = t / BN;  // 0 or 1; chunk i of this thread is plane qf0 + 2*i
-    const bool vn = n0 + nf < g.NCo;
+    // filter: BN columns x QPB planes = NF chunks per thread, column-contiguous across threads
+    int nf[NF], qf[NF];
+    bool vn[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+        const int idx = t + 256 * i;
+        nf[i] = idx % BN;
+        qf[i] = idx / BN;
+        vn[i] = n0 + nf[i] < g.NCo;
+    }
 
-    u32x4 ri[NI], rf[NF];
-    auto load_block = [&](int kh, int e0) {
+    // Two register sets: the loads of block i+2 are issued while block i is computed and are
+    // written to LDS one step later, so they have a whole step of MFMAs (of this and of the
+    // co-resident workgroup) to land.
+    struct StageRegs {
+        u32x4 ri[NI], rf[NF];
+    };
+    StageRegs ra, rb;
+    int kh_l = 0, kb_l = 0;  // next block to load
+    auto load_block = [&](StageRegs &rg) {
+        const bool live = kh_l < g.KH;
+        const int kh = live ? kh_l : 0;
+        const int e0 = live ? e_lo + kb_l * BK : e_hi;  // past the window: every lane out of range
+        u32x4 (&ri)[NI] = rg.ri;
+        u32x4 (&rf)[NF] = rg.rf;
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int hi = ho_[i] + kh - g.pad_h;
@@ -127,26 +159,32 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         }
 #pragma unroll
         for (int i = 0; i < NF; ++i) {
-            const int e = e0 + 8 * (qf0 + 2 * i);
-            const bool ok = vn && e < e_hi;
+            const int e = e0 + 8 * qf[i];
+            const bool ok = vn[i] && e < e_hi;
             const unsigned row = (unsigned)(kh * q_per_kh + ((e - g.e_min) >> 3));
-            const unsigned off = ok ? 16u * (row * (unsigned)g.NCo + (unsigned)(n0 + nf)) : kOutOfRange;
+            const unsigned off = ok ? 16u * (row * (unsigned)g.NCo + (unsigned)(n0 + nf[i])) : kOutOfRange;
             rf[i] = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
         }
+        if (++kb_l == kblocks) {
+            kb_l = 0;
+            ++kh_l;
+        }
     };
-    auto store_block = [&](int stage) {
+    auto store_block = [&](const StageRegs &rg, int stage) {
+        const u32x4 (&ri)[NI] = rg.ri;
+        const u32x4 (&rf)[NF] = rg.rf;
         unsigned char *sf = lds + stage * STAGE;
-        unsigned char *si = sf + QPB * PLANE;
+        unsigned char *si = sf + QPB * PLANE_F;
 #pragma unroll
         for (int i = 0; i < NI; ++i)
-            *reinterpret_cast<u32x4 *>(si + qi * PLANE + (t / QPB + MSTEP * i) * 16) = ri[i];
+            *reinterpret_cast<u32x4 *>(si + qi * PLANE_I + (t / QPB + MSTEP * i) * 16) = ri[i];
 #pragma unroll
         for (int i = 0; i < NF; ++i)
-            *reinterpret_cast<u32x4 *>(sf + (qf0 + 2 * i) * PLANE + nf * 16) = rf[i];
+            *reinterpret_cast<u32x4 *>(sf + qf[i] * PLANE_F + nf[i] * 16) = rf[i];
     };
 
     // ---- accumulators, initialised with the bias through a rank-1 MFMA ----------
-    floatx16_t acc[2][2];
+    floatx16_t acc[TN][2];
     {
         Vec ones;
 #pragma unroll
@@ -156,11 +194,11 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
 #pragma unroll
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < TN; ++nt) {
             Vec bf;
 #pragma unroll
             for (int i = 0; i < 8; ++i) bf[i] = (T)0.0f;
-            const int n = n0 + wn * 64 + nt * 32 + r;
+            const int n = n0 + wn * (BN / 2) + nt * 32 + r;
             if (g.has_bias && hf == 0 && n < g.NCo) bf[0] = bias[n % g.Co];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = TR::mfma(bf, ones, zero);
@@ -168,46 +206,49 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     }
 
     // ---- K loop -----------------------------------------------------------------
-    int kh = 0, kb = 0;  // block being computed
-    if (T_total > 0) {
-        load_block(0, e_lo);
-        store_block(0);
-    }
-    __syncthreads();
-    for (int it = 0; it < T_total; ++it) {
-        int kh_n = kh, kb_n = kb + 1;
-        if (kb_n == kblocks) { kb_n = 0; ++kh_n; }
-        const bool more = it + 1 < T_total;
-        if (more) load_block(kh_n, e_lo + kb_n * BK);
-
-        const unsigned char *sf = lds + (it & 1) * STAGE;
-        const unsigned char *si = sf + QPB * PLANE;
+    auto compute = [&](int stage) {
+        const unsigned char *sf = lds + stage * STAGE;
+        const unsigned char *si = sf + QPB * PLANE_F;
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
             const int qc = 2 * s + hf;
-            Vec af[2], bfv[2];
+            Vec af[TN], bfv[2];
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-                af[nt] = *reinterpret_cast<const Vec *>(sf + qc * PLANE + (wn * 64 + nt * 32 + r) * 16);
+            for (int nt = 0; nt < TN; ++nt)
+                af[nt] = *reinterpret_cast<const Vec *>(sf + qc * PLANE_F + (wn * (BN / 2) + nt * 32 + r) * 16);
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
-                bfv[mt] = *reinterpret_cast<const Vec *>(si + qc * PLANE + (wm * 64 + mt * 32 + r) * 16);
+                bfv[mt] = *reinterpret_cast<const Vec *>(si + qc * PLANE_I + (wm * 64 + mt * 32 + r) * 16);
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
+            for (int nt = 0; nt < TN; ++nt)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = TR::mfma(af[nt], bfv[mt], acc[nt][mt]);
         }
-        if (more) store_block((it + 1) & 1);
+    };
+    // Blocks past the end load nothing (out-of-range offsets) and are never computed.
+    load_block(ra);
+    load_block(rb);
+    store_block(ra, 0);
+    __syncthreads();
+    for (int it = 0; it < T_total; it += 2) {
+        load_block(ra);        // block it+2
+        compute(0);            // block it
+        store_block(rb, 1);    // block it+1
         __syncthreads();
-        kh = kh_n;
-        kb = kb_n;
+        if (it + 1 >= T_total) break;
+        load_block(rb);        // block it+3
+        compute(1);            // block it+1
+        store_block(ra, 0);    // block it+2
+        __syncthreads();
     }
 
-    // ---- epilogue: round, ReLU, transpose through LDS (stages are free after the last barrier) ----
+    // ---- epilogue: round, ReLU, transpose through LDS (stages are free after the last barrier),
+    // 64 pixels (one MFMA tile row per wave) at a time ----
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int mt = 0; mt < 2; ++mt) {
+        if (mt) __syncthreads();  // the first half has been read out
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int nt = 0; nt < TN; ++nt)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 u32x2 pk = {pack2t<TR>(acc[nt][mt][4 * q], acc[nt][mt][4 * q + 1]),
@@ -217,33 +258,36 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
                     const s16x4 z = {0, 0, 0, 0};
                     pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
                 }
-                const int row = wm * 64 + mt * 32 + r;
-                const int col = wn * 64 + nt * 32 + 8 * q + 4 * hf;
+                const int row = wm * 32 + r;  // pixel wm*64 + mt*32 + r of the tile
+                const int col = wn * (BN / 2) + nt * 32 + 8 * q + 4 * hf;
                 *reinterpret_cast<u32x2 *>(lds + row * EPITCH + col * 2) = pk;
             }
-    __syncthreads();
+        __syncthreads();
+        constexpr int CPR = BN / 8;  // 16-byte chunks per row
 #pragma unroll
-    for (int i = 0; i < (BM * BN / 8) / 256; ++i) {
-        const int idx = i * 256 + t;
-        const int row = idx >> 4, ch = idx & 15;
-        const unsigned m = m0 + (unsigned)row;
-        const int n = n0 + 8 * ch;
-        if (m < (unsigned)g.M && n < g.NCo) {
-            const unsigned wo = m % (unsigned)g.Wf_out;
-            const unsigned rowid = m / (unsigned)g.Wf_out;
-            const unsigned oc = wo * (unsigned)g.NCo + (unsigned)n;
-            if (oc + 8u <= (unsigned)g.out_row) {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * EPITCH + ch * 16);
-                const unsigned long long off8 = ((unsigned long long)rowid * (unsigned)g.out_row + oc) >> 3;
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
+        for (int i = 0; i < (64 * CPR) / 256; ++i) {
+            const int idx = i * 256 + t;
+            const int row = idx / CPR, ch = idx % CPR;
+            const unsigned m = m0 + (unsigned)((row >> 5) * 64 + mt * 32 + (row & 31));
+            const int n = n0 + 8 * ch;
+            if (m < (unsigned)g.M && n < g.NCo) {
+                const unsigned wo = m % (unsigned)g.Wf_out;
+                const unsigned rowid = m / (unsigned)g.Wf_out;
+                const unsigned oc = wo * (unsigned)g.NCo + (unsigned)n;
+                if (oc + 8u <= (unsigned)g.out_row) {
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * EPITCH + ch * 16);
+                    const unsigned long long off8 = ((unsigned long long)rowid * (unsigned)g.out_row + oc) >> 3;
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
+                }
             }
         }
     }
 }
 
-template <typename TR>
+template <typename TR, int TN>
 int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
+    constexpr int BN = 64 * TN;
     TiledArgs a;
     a.tiles_n = (unsigned)((g.NCo + BN - 1) / BN);
     a.tiles_m = (unsigned)((g.M + BM - 1) / BM);
@@ -255,10 +299,15 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
     a.wp_bytes = (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
     const unsigned blocks = a.per_xcd * 8;
     if (g.relu)
-        conv_tiled_kernel<TR, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+        conv_tiled_kernel<TR, TN, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     else
-        conv_tiled_kernel<TR, false><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+        conv_tiled_kernel<TR, TN, false><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     return (int)hipGetLastError();
+}
+
+template <typename TR>
+int launch_any(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
+    return fc_tiled_bn(g) == 256 ? launch<TR, 4>(g, x, wp, bias, y, st) : launch<TR, 2>(g, x, wp, bias, y, st);
 }
 
 }  // namespace
@@ -266,7 +315,7 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
 int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
                          void *y, void *stream) {
     hipStream_t st = (hipStream_t)stream;
-    if (dt == FOLDCONV_F16) return launch<F16Traits>(g, x, w_pack, bias, y, st);
-    if (dt == FOLDCONV_BF16) return launch<BF16Traits>(g, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_F16) return launch_any<F16Traits>(g, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16) return launch_any<BF16Traits>(g, x, w_pack, bias, y, st);
     return (int)hipErrorInvalidValue;
 }

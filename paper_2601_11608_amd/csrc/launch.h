@@ -38,5 +38,6 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
 int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
                          void *y, void *stream);
 bool fc_tiled_ok(const ConvGeom &g);
+int fc_tiled_bn(const ConvGeom &g);  // output columns per workgroup tile of the tiled kernel: 128 or 256
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,
                           void *y, void *stream);

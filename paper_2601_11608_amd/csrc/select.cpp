@@ -36,6 +36,12 @@ static bool vector_ok(const ConvGeom &g) {
 
 bool fc_tiled_ok(const ConvGeom &g) { return vector_ok(g); }
 
+int fc_tiled_bn(const ConvGeom &g) {
+    // The 256-column tile when it wastes no more columns than the 128-column one would.
+    const int pad128 = (g.NCo + 127) / 128 * 128, pad256 = (g.NCo + 255) / 256 * 256;
+    return (g.NCo >= 256 && pad256 <= pad128) ? 256 : 128;
+}
+
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     if (!vector_ok(g)) return false;
     // exact multiply-high division of (tile start + lane) by the folded width and by the output height
@@ -77,7 +83,7 @@ int fc_band_tile_n(int kernel, const ConvGeom &g) {
     StreamShape sh;
     switch (kernel) {
         case FC_KERNEL_STREAM: return fc_stream_shape(g, 1, &sh) ? 32 * sh.nt : 32;
-        case FC_KERNEL_TILED: return 128;
+        case FC_KERNEL_TILED: return fc_tiled_bn(g);
         default: return 32;
     }
 }

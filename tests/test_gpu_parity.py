@@ -81,8 +81,10 @@ SMALL = [
     (1, 5, 8, 68, 132, 3, 3, 1, 4, True, True),     # FC=272, NCo=528: K too large for the streaming kernel
     (2, 3, 8, 132, 40, 3, 3, 1, 4, False, False),   # FC=528, NCo=160: ragged N tile of the tiled kernel
     (1, 20, 28, 68, 32, 3, 3, 1, 4, True, True),    # several 128-pixel M tiles, ragged last one
-    (2, 65, 1024, 3, 64, 3, 3, 1, 16, True, True),  # 8320 folded pixels: the workgroup-cooperative store path
-    (3, 50, 480, 12, 48, 3, 3, 1, 4, False, False), # same, 3 column groups per workgroup (NCo = 192)
+    (1, 6, 16, 68, 64, 3, 3, 1, 4, True, True),     # NCo = 256: the 256-column tile of the tiled kernel
+    (1, 20, 28, 132, 256, 3, 3, 1, 4, False, True), # NCo = 1024, several M tiles with a ragged last one
+    (2, 65, 1024, 3, 64, 3, 3, 1, 16, True, True),  # 8320 folded pixels, many tiles per wave of the streaming kernel
+    (3, 50, 480, 12, 48, 3, 3, 1, 4, False, False), # same with NCo = 192 (3 column groups)
 ]
 
 
