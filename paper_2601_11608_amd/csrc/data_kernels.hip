@@ -50,25 +50,18 @@ expand_filter_kernel(const U *__restrict__ w, U *__restrict__ we, int KH, int KW
 }
 
 // ---------------------------------------------------------------------------
-// Straight copy, 16 bytes per lane per access, four independent accesses in
-// flight per lane.  The width fold of a contiguous NHWC tensor is this copy
+// Straight copy, 16 bytes per lane, one access per lane: 4 KB per workgroup, and as many
+// workgroups as there are 4 KB pieces.  The hardware dispatcher hands the pieces out in address
+// order, which keeps the chip-wide read and write fronts compact; on MI355X this measured
+// 6.6 TB/s against 5.4-6.0 TB/s for persistent grid-stride forms of the same copy.
+// The width fold of a contiguous NHWC tensor is this copy
 // (paper: Eq. "width_fold_def"; equal linear offsets before and after).
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kThreads)
 copy16_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, long long n16) {
     const long long stride = (long long)gridDim.x * kThreads;
-    long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        u32x4 a = __builtin_nontemporal_load(src + i);
-        u32x4 b = __builtin_nontemporal_load(src + i + stride);
-        u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride);
-        u32x4 d = __builtin_nontemporal_load(src + i + 3 * stride);
-        __builtin_nontemporal_store(a, dst + i);
-        __builtin_nontemporal_store(b, dst + i + stride);
-        __builtin_nontemporal_store(c, dst + i + 2 * stride);
-        __builtin_nontemporal_store(d, dst + i + 3 * stride);
-    }
-    for (; i < n16; i += stride) dst[i] = src[i];
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 __global__ void __launch_bounds__(kThreads)
@@ -182,8 +175,7 @@ int fc_launch_copy(const void *src, void *dst, size_t bytes, void *stream) {
     if (((uintptr_t)src | (uintptr_t)dst) % 16 == 0) {
         const long long n16 = (long long)(bytes / 16);
         if (n16 > 0) {
-            // 4 x 16 B per lane per trip; enough blocks to cover all 256 CUs several times over.
-            const unsigned grid = blocks_for(n16, kThreads * 4, 256 * 16);
+            const unsigned grid = blocks_for(n16, kThreads, 1 << 22);
             copy16_kernel<<<grid, kThreads, 0, st>>>((const u32x4 *)src, (u32x4 *)dst, n16);
         }
         const size_t tail = bytes % 16;
@@ -204,15 +196,15 @@ int fc_launch_unfold(const foldconv_plan_s *p, const void *y_fold, void *y, void
     const long long src_row_b = (long long)s.W_out_fold * s.Co_fold * s.elem_bytes;
     const long long dst_row_b = (long long)s.W_out * s.C_out * s.elem_bytes;
     if (src_row_b % 16 == 0 && dst_row_b % 16 == 0 && ((uintptr_t)y_fold | (uintptr_t)y) % 16 == 0) {
-        const unsigned grid = blocks_for(rows * (dst_row_b / 16), kThreads, 256 * 32);
+        const unsigned grid = blocks_for(rows * (dst_row_b / 16), kThreads, 1 << 22);
         crop_rows_kernel<u32x4><<<grid, kThreads, 0, st>>>((const u32x4 *)y_fold, (u32x4 *)y, rows,
                                                            (int)(src_row_b / 16), (int)(dst_row_b / 16));
     } else if (s.elem_bytes == 2) {
-        const unsigned grid = blocks_for(rows * (dst_row_b / 2), kThreads, 256 * 32);
+        const unsigned grid = blocks_for(rows * (dst_row_b / 2), kThreads, 1 << 22);
         crop_rows_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)y_fold, (uint16_t *)y, rows,
                                                               (int)(src_row_b / 2), (int)(dst_row_b / 2));
     } else {
-        const unsigned grid = blocks_for(rows * (dst_row_b / 4), kThreads, 256 * 32);
+        const unsigned grid = blocks_for(rows * (dst_row_b / 4), kThreads, 1 << 22);
         crop_rows_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)y_fold, (uint32_t *)y, rows,
                                                               (int)(src_row_b / 4), (int)(dst_row_b / 4));
     }
@@ -224,7 +216,7 @@ int fc_launch_pad_input(const foldconv_plan_s *p, const void *x, void *x_pad, vo
     hipStream_t st = (hipStream_t)stream;
     const long long pixels = (long long)s.N * s.H * s.W;
     const long long chunks = pixels * s.C_pad * s.elem_bytes / 16;
-    const unsigned grid = blocks_for(chunks, kThreads, 256 * 32);
+    const unsigned grid = blocks_for(chunks, kThreads, 1 << 22);
     if (s.elem_bytes == 2)
         pad_input_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)x, (uint16_t *)x_pad, pixels, s.C_in, s.C_pad);
     else
