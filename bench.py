@@ -198,6 +198,21 @@ def main():
         extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,
                               "useful_pct_of_mfma_peak": 100.0 * flops5 / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                               "kernels": [["gather", "tiled", "stream"][L5.plan.shapes.conv_kernel] for L5 in stack.layers]}
+        # tall-skinny GEMM as a folded 1x1 convolution: A[2^21, 12] x B[12, 64], fp16, F = 4
+        Mg, Kg, Ng, Fg = 1 << 21, 12, 64, 4
+        gp = fc.foldconv_plan_gemm(Mg, Kg, Ng, Fg, torch.float16)
+        gs = gp.shapes
+        gl = wl.Layer("gemm", 1, gs.H, gs.W, Kg, Ng, 1, 1, 0, Fg, "f16", False, "normal")
+        gx, gw, _ = wl.make_layer(gl, 2001)
+        G = runner.FoldedLayer(gl, gw, None)
+        gxd = gx.cuda()
+        gy = G.new_output()
+        _, g_ms = time_events(lambda: G.forward(gxd, gy), 50, 5)
+        _, gp_ms = time_events(lambda: G.forward_padded(gxd, gy), 20, 3)
+        extras["gemm_1x1"] = {"M": Mg, "K": Kg, "N": Ng, "F": Fg, "ms": g_ms, "padded_ms": gp_ms,
+                              "useful_tflops": gs.useful_flops / (g_ms * 1e-3) / 1e12,
+                              "GBps": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9,
+                              "frac_of_hbm_peak": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

@@ -105,6 +105,32 @@ typedef struct foldconv_shapes_s {
 FOLDCONV_API int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
                   int fold_factor, foldconv_dtype_t dtype, foldconv_plan_t *out);
 
+/*
+ * Plan for a tall-skinny matrix product C[M][N] = A[M][K] * B[K][N] run as a
+ * width-folded 1x1 convolution: A is the input x[1][1][M][K] (row-major A is
+ * already that tensor), B is the filter w[1][1][K][N], C is y[1][1][M][N];
+ * folding F rows of A into one pixel gives F*K aligned channels and the
+ * expanded filter is the paper's block diagonal I_F (x) B.  M must be
+ * divisible by F.  The returned plan is used with the same calls as any other
+ * (expand, fold, forward, conv_padded_forward).
+ * paper: section "Generalization to GEMM via 1x1 Convolution".
+ */
+FOLDCONV_API int foldconv_plan_gemm(long long M, int K, int N, int fold_factor, foldconv_dtype_t dtype,
+                                    foldconv_plan_t *out);
+
+/*
+ * Fold-factor choice: among the power-of-two factors F <= 64 that divide W,
+ * the one with the smallest estimated time max(HBM bytes / sustained HBM rate,
+ * issued MFMA flops / sustained MFMA rate), where a factor that leaves F*C_in
+ * off the 16-byte chunk alignment is charged the element-gather kernel's
+ * rate; ties go to the smaller F.  *fold_factor receives the choice (1 = do not fold).
+ * paper: "F is chosen to align with Tensor core tile sizes"; the "lightweight
+ * cost model ... channel size, tensor core tile alignment, and arithmetic
+ * intensity" of the MLIR section.  Host only.
+ */
+FOLDCONV_API int foldconv_choose_fold(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
+                                      foldconv_dtype_t dtype, int *fold_factor);
+
 /* Copy the plan's derived shapes into *out (host memory of the caller). */
 FOLDCONV_API int foldconv_plan_query(foldconv_plan_t plan, foldconv_shapes_t *out);
 

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     foldconv_forward,
     foldconv_pack_filter,
     foldconv_plan,
+    foldconv_plan_gemm,
+    foldconv_choose_fold,
     foldconv_plan_destroy,
     foldconv_plan_query,
     foldconv_strerror,

@@ -69,6 +69,10 @@ def load_library():
     vp, sz, ui, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint, ctypes.c_int
     lib.foldconv_plan.argtypes = [ci] * 10 + [ctypes.POINTER(vp)]
     lib.foldconv_plan.restype = ci
+    lib.foldconv_plan_gemm.argtypes = [ctypes.c_longlong, ci, ci, ci, ci, ctypes.POINTER(vp)]
+    lib.foldconv_plan_gemm.restype = ci
+    lib.foldconv_choose_fold.argtypes = [ci] * 9 + [ctypes.POINTER(ci)]
+    lib.foldconv_choose_fold.restype = ci
     lib.foldconv_plan_query.argtypes = [vp, ctypes.POINTER(Shapes)]
     lib.foldconv_plan_query.restype = ci
     lib.foldconv_plan_destroy.argtypes = [vp]
@@ -134,6 +138,22 @@ def foldconv_plan(N, H, W, C_in, C_out, KH, KW, pad, fold_factor, dtype):
     plan = Plan(h, None)
     plan.shapes = foldconv_plan_query(plan)
     return plan
+
+
+def foldconv_plan_gemm(M, K, N, fold_factor, dtype):
+    lib = load_library()
+    h = ctypes.c_void_p()
+    _check(lib.foldconv_plan_gemm(M, K, N, fold_factor, _dtype_code(dtype), ctypes.byref(h)), "foldconv_plan_gemm")
+    plan = Plan(h, None)
+    plan.shapes = foldconv_plan_query(plan)
+    return plan
+
+
+def foldconv_choose_fold(N, H, W, C_in, C_out, KH, KW, pad, dtype):
+    f = ctypes.c_int(1)
+    _check(load_library().foldconv_choose_fold(N, H, W, C_in, C_out, KH, KW, pad, _dtype_code(dtype),
+                                               ctypes.byref(f)), "foldconv_choose_fold")
+    return f.value
 
 
 def foldconv_plan_query(plan):

@@ -131,6 +131,57 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     return FOLDCONV_OK;
 }
 
+extern "C" int foldconv_plan_gemm(long long M, int K, int N, int fold_factor, foldconv_dtype_t dtype,
+                                  foldconv_plan_t *out) {
+    if (!out) return FOLDCONV_ERR_BADARG;
+    *out = nullptr;
+    if (M <= 0 || M > INT_MAX) return M <= 0 ? FOLDCONV_ERR_BADARG : FOLDCONV_ERR_UNSUPPORTED;
+    if (fold_factor <= 0) return FOLDCONV_ERR_BADARG;
+    if (M % fold_factor != 0) return FOLDCONV_ERR_INDIVISIBLE;
+    // paper, "GEMM as a 1x1 Convolution": rows of A are spatial positions with K channels.  A 1x1
+    // kernel couples no two positions, so the M rows may be laid out as any H x W image; the
+    // synthetic width is taken as F times the largest divisor of M/F up to 16384, which keeps
+    // image rows short enough for the vector kernels' row arithmetic.
+    const long long Mf = M / fold_factor;
+    long long d = Mf < 16384 ? Mf : 16384;
+    while (Mf % d != 0) --d;
+    return foldconv_plan(1, (int)(Mf / d), (int)(d * fold_factor), K, N, 1, 1, 0, fold_factor, dtype, out);
+}
+
+extern "C" int foldconv_choose_fold(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
+                                    foldconv_dtype_t dtype, int *fold_factor) {
+    if (!fold_factor) return FOLDCONV_ERR_BADARG;
+    *fold_factor = 1;
+    double best = -1.0;
+    int status = FOLDCONV_ERR_BADARG;
+    for (int F = 1; F <= 64; F *= 2) {
+        if (W % F != 0) break;
+        foldconv_plan_t p = nullptr;
+        const int st = foldconv_plan(N, H, W, C_in, C_out, KH, KW, pad, F, dtype, &p);
+        if (st != FOLDCONV_OK) {
+            if (F == 1) return st;
+            continue;
+        }
+        status = FOLDCONV_OK;
+        const foldconv_shapes_t &s = p->s;
+        const double bytes = (double)s.x_bytes + (double)s.y_bytes + (double)s.w_exp_bytes;
+        // sustained rates measured on MI355X with these kernels: 5.4 TB/s of the 8 TB/s HBM peak,
+        // 0.7 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
+        // element-gather kernel that serves unaligned channel counts issues about 0.02 PFLOP/s
+        const double t_hbm = bytes / 5.4e12;
+        double rate = dtype == FOLDCONV_F32 ? 0.7e15 / 16.0 : 0.7e15;
+        if (s.conv_kernel == FC_KERNEL_GATHER) rate = 0.02e15;
+        const double t_mfma = s.issued_flops_band / rate;
+        const double t = t_hbm > t_mfma ? t_hbm : t_mfma;
+        if (best < 0.0 || t < best * (1.0 - 1e-9)) {
+            best = t;
+            *fold_factor = F;
+        }
+        foldconv_plan_destroy(p);
+    }
+    return status;
+}
+
 extern "C" int foldconv_plan_query(foldconv_plan_t plan, foldconv_shapes_t *out) {
     if (!plan || plan->magic != FOLDCONV_MAGIC || !out) return FOLDCONV_ERR_BADARG;
     *out = plan->s;

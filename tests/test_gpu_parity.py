@@ -185,3 +185,20 @@ def test_empty_bias_and_relu_flags(fc, oracle):
     assert torch.equal(y, b.expand(N, H, W, Co))
     y = run_folded(fc, plan, x, w, b, fc.FLAG_RELU)
     assert torch.equal(y, torch.relu(b).expand(N, H, W, Co))
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("M,K,N,F", [(4096, 12, 64, 4), (1000, 3, 40, 8), (8192 * 3, 5, 16, 8), (777, 24, 8, 1)])
+def test_gemm_as_folded_one_by_one_conv(fc, oracle, M, K, N, F, dt):
+    """paper: "Generalization to GEMM via 1x1 Convolution": C = A B with tall-skinny A."""
+    A = draw((M, K), dt, 21)
+    B = (draw((K, N), dt, 22) * (1.0 / np.sqrt(K))).to(TORCH_DT[dt])
+    plan = fc.foldconv_plan_gemm(M, K, N, F, A.dtype)
+    s = plan.shapes
+    x = A.reshape(1, s.H, s.W, K)
+    w = B.reshape(1, 1, K, N)
+    ref = oracle.conv_direct(f64(x), f64(w), None, 0, 0).reshape(1, M, N)     # pinned to A @ B in the oracle tests
+    y = run_folded(fc, plan, x, w, None, 0).reshape(1, M, N)
+    assert rel_l2_per_image(f64(y), ref) <= TOL[dt]
+    yp = run_padded(fc, plan, x, w, None, 0).reshape(1, M, N)
+    assert rel_l2_per_image(f64(yp), ref) <= TOL[dt]

@@ -159,3 +159,38 @@ def test_workloads_shapes():
     assert tuple(x.shape) == (2, 1, 16000, 1) and tuple(ws[0].shape) == (1, 9, 1, 64)
     layers, x2, ws2, _ = wl.make_config("c4", N=2)
     assert (x2 == x).all() and (ws2[0] == ws[0]).all()      # seeded
+
+
+def test_gemm_plan_is_a_folded_one_by_one_conv(fc):
+    """paper: "Generalization to GEMM via 1x1 Convolution"."""
+    p = fc.foldconv_plan_gemm(1 << 20, 12, 64, 4, "float16")
+    s = p.shapes
+    assert (s.KH, s.KW, s.pad_h, s.pad_w, s.KW_fold, s.d_min, s.d_max) == (1, 1, 0, 0, 1, 0, 0)
+    assert s.N * s.H * s.W == 1 << 20 and s.W % 4 == 0 and s.C_in == 12 and s.C_out == 64
+    assert (s.C_fold, s.Co_fold) == (48, 256) and s.unfold_is_alias == 1
+    assert s.useful_flops == 2.0 * (1 << 20) * 12 * 64
+    assert s.x_bytes == (1 << 20) * 12 * 2 and s.y_bytes == (1 << 20) * 64 * 2
+    assert s.W_out_fold < 65000            # rows short enough for the vector kernels
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_plan_gemm(1001, 12, 64, 4, "float16")
+    assert e.value.status == -2
+    # a prime row count still plans (one long image row)
+    s = fc.foldconv_plan_gemm(7919, 8, 16, 1, "float16").shapes
+    assert s.H * s.W == 7919
+
+
+def test_fold_factor_choice(fc):
+    """Cost model: fold small misaligned C_in up to the chunk alignment, leave aligned wide layers alone."""
+    # C_in = 3: no factor below 8 makes F*C_in a multiple of 8
+    assert fc.foldconv_choose_fold(64, 224, 224, 3, 64, 3, 3, 1, "float16") == 8
+    assert fc.foldconv_choose_fold(16, 1, 16000, 1, 64, 1, 9, 4, "float16") == 8
+    assert fc.foldconv_choose_fold(32, 112, 112, 12, 48, 3, 3, 1, "bfloat16") == 2
+    # already aligned and MFMA-bound: folding only adds structural zeros
+    assert fc.foldconv_choose_fold(8, 56, 56, 64, 64, 3, 3, 1, "float16") == 1
+    assert fc.foldconv_choose_fold(32, 112, 112, 132, 256, 3, 3, 1, "bfloat16") == 2     # 132 -> 264 = 33 * 8
+    # width not divisible by 2: nothing to choose from
+    assert fc.foldconv_choose_fold(1, 8, 9, 3, 4, 3, 3, 1, "float16") == 1
+    for F in (8, 16):                      # every choice must be a legal plan
+        fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, F, "float16")
+    lib = fc.load_library()
+    assert lib.foldconv_choose_fold(1, 8, 8, 3, 4, 3, 3, 1, 1, None) == -1

@@ -420,3 +420,18 @@ def test_axis_pad_convention(oracle):
     assert oracle.axis_pads(1, 9, 4) == (0, 4)
     assert oracle.axis_pads(5, 1, 2) == (2, 0)
     assert oracle.axis_pads(1, 1, 3) == (0, 0)
+
+
+def test_one_by_one_conv_is_matmul(oracle):
+    """paper: "GEMM as a 1x1 Convolution" -- A[M,K] as x[1,1,M,K], B[K,N] as w[1,1,K,N]."""
+    r = rng(30)
+    A = r.standard_normal((24, 5)); B = r.standard_normal((5, 7))
+    y = oracle.conv_direct(A.reshape(1, 1, 24, 5), B.reshape(1, 1, 5, 7), None, 0, 0)
+    assert np.allclose(y.reshape(24, 7), A @ B, rtol=0, atol=1e-13)
+    # folding rows of A into channels leaves the product unchanged; the expanded filter is I_F (x) B
+    yr, parts = oracle.conv_rewrite(A.reshape(1, 1, 24, 5), B.reshape(1, 1, 5, 7), None, 0, 0, 4, return_parts=True)
+    assert np.max(np.abs(yr.reshape(24, 7) - A @ B)) <= 1e-12
+    assert np.array_equal(parts["we"][0, 0], np.kron(np.eye(4), B))
+    # any H x W layout of the M rows gives the same product (a 1x1 kernel couples no two positions)
+    y2 = oracle.conv_direct(A.reshape(1, 4, 6, 5), B.reshape(1, 1, 5, 7), None, 0, 0)
+    assert np.array_equal(y2.reshape(24, 7), y.reshape(24, 7))
