@@ -165,6 +165,13 @@ def main():
 
         _, r_ms = time_events(step_repack, max(3, args.steps // 5), 2)
         extras["with_filter_repack_ms"] = r_ms
+        # compact filter storage (non-zero blocks of w' only), headline layer and the stack below
+        def step_compact():
+            L.forward(xd, y, compact=True)
+
+        _, c_ms = time_events(step_compact, max(3, args.steps // 5), 2)
+        extras["compact_filter"] = {"kernel_ms": c_ms, "filter_bytes": int(s.filter_compact_bytes),
+                                    "expanded_filter_bytes": int(s.w_exp_bytes)}
         # materialised fold and reconstruct copies (not on the timed path: both alias)
         nbuf = 8
         xs_rot = [torch.empty_like(xd) for _ in range(nbuf)]
@@ -195,7 +202,11 @@ def main():
         flops5 = sum(L5.plan.shapes.useful_flops for L5 in stack.layers)
         _, s_ms = time_events(lambda: stack.forward(x5d), 10, 2)
         _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 10, 2)
-        extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,
+        _, sc_ms = time_events(lambda: stack.forward(x5d, compact=True), 10, 2)
+        extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "folded_compact_filter_ms": sc_ms,
+                              "filter_bytes": {"expanded": sum(int(L5.plan.shapes.w_exp_bytes) for L5 in stack.layers),
+                                               "compact": sum(int(L5.plan.shapes.filter_compact_bytes) for L5 in stack.layers)},
+                              "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,
                               "useful_pct_of_mfma_peak": 100.0 * flops5 / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                               "kernels": [["gather", "tiled", "stream"][L5.plan.shapes.conv_kernel] for L5 in stack.layers]}
         # tall-skinny GEMM as a folded 1x1 convolution: A[2^21, 12] x B[12, 64], fp16, F = 4

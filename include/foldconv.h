@@ -63,9 +63,12 @@ enum {
                                          instead of only the band that can be non-zero for the
                                          output slots of a tile.  Same result for finite data. */
     FOLDCONV_FLAG_KEEP_FOLDED = 4u,   /* write y' [N][H_out][W'_out][F*C_out], not y           */
-    FOLDCONV_FLAG_FILTER_PACKED = 8u  /* workspace already holds the packed filter written by a
+    FOLDCONV_FLAG_FILTER_PACKED = 8u, /* workspace already holds the packed filter written by a
                                          previous call with the same plan and the same filter
                                          (weights are static after training): skip re-packing  */
+    FOLDCONV_FLAG_FILTER_COMPACT = 16u /* workspace holds the compact filter written by
+                                         foldconv_pack_filter_compact (only the non-zero blocks
+                                         of w'); w_exp is not read and may be NULL              */
 };
 
 /* Everything a caller needs to size buffers and to report throughput. */
@@ -88,6 +91,8 @@ typedef struct foldconv_shapes_s {
     int64_t x_bytes, w_bytes, bias_bytes, w_exp_bytes, y_bytes, y_fold_bytes;
     int64_t workspace_bytes;        /* for foldconv_forward / foldconv_pack_filter            */
     int64_t padded_workspace_bytes; /* for conv_padded_forward                                */
+    int64_t filter_compact_bytes;   /* for foldconv_pack_filter_compact and foldconv_forward
+                                       with FOLDCONV_FLAG_FILTER_COMPACT                      */
     double useful_flops;            /* 2*N*H_out*W_out*C_out*KH*KW*C_in                       */
     double issued_flops_dense;      /* MFMA flops issued with FOLDCONV_FLAG_DENSE_K           */
     double issued_flops_band;       /* MFMA flops issued by the default band walk             */
@@ -174,6 +179,22 @@ FOLDCONV_API int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, v
                          size_t workspace_bytes, void *stream);
 
 /*
+ * Compact storage of the expanded filter: only the non-zero blocks of w' are
+ * kept.  Every output slot g uses the same KW*C_in x C_out tap matrix per kh,
+ * placed (g-p)*C_in rows into the folded K window; the workspace receives one
+ * zero-padded copy of that matrix per kh and per alignment of the placement
+ * against the kernels' 8-row chunks (8/gcd(C_in,8) copies), built straight
+ * from the ORIGINAL filter w [KH][KW][C_in][C_out] -- w' is never materialised.
+ * Size: shapes.filter_compact_bytes (about KW/(KW'*F) of w').  Use the
+ * workspace with foldconv_forward and FOLDCONV_FLAG_FILTER_COMPACT; results
+ * are bit-identical to the packed-w' route.
+ * paper: section "Potential Optimizations for Sparsity and Quantization"
+ * (store just the non-zero blocks of the block-structured filter).
+ */
+FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *w, void *workspace,
+                                              size_t workspace_bytes, void *stream);
+
+/*
  * Folded convolution + bias (+ReLU) + reconstruct:
  *   y'[n][h][w'][g*C_out+co] = b[co] + sum_{kh,d,c'} x'[n][h+kh-pad_h][w'+d][c'] * w'[kh][d-d_min][c'][g*C_out+co]
  * with out-of-range x' read as zero, fp32 accumulation, one rounding to the
@@ -181,7 +202,8 @@ FOLDCONV_API int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, v
  * FOLDCONV_FLAG_KEEP_FOLDED.  paper: Eq. "new_conv_H"; Eq. "bias_construct"
  * (the replicated bias is read as b[n mod C_out]); Reconstruct step.
  * bias may be NULL.  workspace: shapes.workspace_bytes, 256-byte aligned,
- * may be NULL when that is 0.
+ * may be NULL when that is 0; with FOLDCONV_FLAG_FILTER_COMPACT it is the
+ * compact filter (shapes.filter_compact_bytes) and w_exp is ignored.
  */
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,

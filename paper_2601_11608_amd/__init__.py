@@ -5,6 +5,7 @@ library is loaded on first use; importing the package loads nothing.
 """
 from .binding import (  # noqa: F401
     FLAG_DENSE_K,
+    FLAG_FILTER_COMPACT,
     FLAG_FILTER_PACKED,
     FLAG_KEEP_FOLDED,
     FLAG_RELU,
@@ -15,6 +16,7 @@ from .binding import (  # noqa: F401
     foldconv_fold_input,
     foldconv_forward,
     foldconv_pack_filter,
+    foldconv_pack_filter_compact,
     foldconv_plan,
     foldconv_plan_gemm,
     foldconv_choose_fold,

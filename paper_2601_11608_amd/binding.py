@@ -15,6 +15,7 @@ FLAG_RELU = 1
 FLAG_DENSE_K = 2
 FLAG_KEEP_FOLDED = 4
 FLAG_FILTER_PACKED = 8
+FLAG_FILTER_COMPACT = 16
 
 _DTYPE_CODE = {"float32": 0, "float16": 1, "bfloat16": 2}
 
@@ -36,7 +37,7 @@ class Shapes(ctypes.Structure):
             "padded_kernel")]
         + [(n, ctypes.c_int64) for n in (
             "gemm_M", "gemm_N", "gemm_K", "x_bytes", "w_bytes", "bias_bytes", "w_exp_bytes", "y_bytes",
-            "y_fold_bytes", "workspace_bytes", "padded_workspace_bytes")]
+            "y_fold_bytes", "workspace_bytes", "padded_workspace_bytes", "filter_compact_bytes")]
         + [(n, ctypes.c_double) for n in (
             "useful_flops", "issued_flops_dense", "issued_flops_band", "issued_flops_padded")]
     )
@@ -85,6 +86,8 @@ def load_library():
     lib.foldconv_unfold_output.restype = ci
     lib.foldconv_pack_filter.argtypes = [vp, vp, vp, sz, vp]
     lib.foldconv_pack_filter.restype = ci
+    lib.foldconv_pack_filter_compact.argtypes = [vp, vp, vp, sz, vp]
+    lib.foldconv_pack_filter_compact.restype = ci
     lib.foldconv_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, ui, vp]
     lib.foldconv_forward.restype = ci
     lib.conv_padded_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, ui, vp]
@@ -226,10 +229,18 @@ def foldconv_pack_filter(plan, w_exp, workspace, stream=None):
                                                _stream(stream)), "foldconv_pack_filter")
 
 
+def foldconv_pack_filter_compact(plan, w, workspace, stream=None):
+    s = plan.shapes
+    _need(w, s.w_bytes, "w")
+    _check(load_library().foldconv_pack_filter_compact(plan.handle, _ptr(w), _ptr(workspace), _nbytes(workspace),
+                                                       _stream(stream)), "foldconv_pack_filter_compact")
+
+
 def foldconv_forward(plan, x_fold, w_exp, bias, y, workspace=None, flags=0, stream=None):
     s = plan.shapes
     _need(x_fold, s.x_bytes, "x_fold")
-    _need(w_exp, s.w_exp_bytes, "w_exp")
+    if not (flags & FLAG_FILTER_COMPACT):
+        _need(w_exp, s.w_exp_bytes, "w_exp")
     _need(bias, s.bias_bytes, "bias")
     _need(y, s.y_fold_bytes if (flags & FLAG_KEEP_FOLDED) else s.y_bytes, "y")
     _check(load_library().foldconv_forward(plan.handle, _ptr(x_fold), _ptr(w_exp), _ptr(bias), _ptr(y),

@@ -10,7 +10,8 @@ static bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 static int hip_status(int e) { return e == 0 ? FOLDCONV_OK : FOLDCONV_ERR_HIP; }
 
 static const unsigned kAllFlags =
-    FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED;
+    FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED |
+    FOLDCONV_FLAG_FILTER_COMPACT;
 
 extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
     if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
@@ -50,13 +51,27 @@ extern "C" int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, voi
     return hip_status(fc_launch_pack(plan->fold, plan->s.elem_bytes, w_exp, workspace, stream));
 }
 
+extern "C" int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *w, void *workspace,
+                                            size_t workspace_bytes, void *stream) {
+    if (!plan_ok(plan) || !w || w == workspace) return FOLDCONV_ERR_BADARG;
+    int st = check_ws(workspace, workspace_bytes, plan->s.filter_compact_bytes);
+    if (st) return st;
+    if (!aligned(w, (size_t)plan->s.elem_bytes)) return FOLDCONV_ERR_BADARG;
+    // The gather kernel indexes the original filter itself: its compact form is a copy of w.
+    if (plan->s.conv_kernel == FC_KERNEL_GATHER)
+        return hip_status(fc_launch_copy(w, workspace, (size_t)plan->s.w_bytes, stream));
+    return hip_status(fc_launch_compact(plan->fold, plan->s.elem_bytes, w, workspace, stream));
+}
+
 extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, const void *bias,
                                 void *y, void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
-    if (!plan_ok(plan) || !x_fold || !w_exp || !y) return FOLDCONV_ERR_BADARG;
+    if (!plan_ok(plan) || !x_fold || !y) return FOLDCONV_ERR_BADARG;
     if (flags & ~kAllFlags) return FOLDCONV_ERR_BADARG;
+    const bool compact = (flags & FOLDCONV_FLAG_FILTER_COMPACT) != 0;
+    if (!compact && !w_exp) return FOLDCONV_ERR_BADARG;
     const foldconv_shapes_t &s = plan->s;
     const size_t eb = (size_t)s.elem_bytes;
-    if (!aligned(x_fold, eb) || !aligned(w_exp, eb) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
+    if (!aligned(x_fold, eb) || (!compact && !aligned(w_exp, eb)) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
         return FOLDCONV_ERR_BADARG;
     ConvGeom g = plan->fold;
     g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
@@ -65,6 +80,15 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
     g.out_row = (flags & FOLDCONV_FLAG_KEEP_FOLDED) ? g.Wf_out * g.NCo : s.W_out * s.C_out;
 
     int kernel = s.conv_kernel;
+    if (compact) {
+        // every kernel takes its filter operand from the workspace
+        int st = check_ws(workspace, workspace_bytes, s.filter_compact_bytes);
+        if (st) return st;
+        if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
+        g.compact = 1;
+        return hip_status(
+            fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, workspace, workspace, bias, y, stream));
+    }
     if (kernel != FC_KERNEL_GATHER) {
         int st = check_ws(workspace, workspace_bytes, s.workspace_bytes);
         if (st) return st;

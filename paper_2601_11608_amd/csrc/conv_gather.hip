@@ -4,7 +4,8 @@
 // that the result is still the folded convolution).  One wave owns one
 // 32 (output columns n) x 32 (output pixels m) tile and walks
 // K = (kh, extended channel e) straight from global memory; the filter is
-// read in its canonical [KH][KW'][F*C_in][F*C_out] layout.
+// read in its canonical [KH][KW'][F*C_in][F*C_out] layout, or, as compact
+// storage, straight from the original [KH][KW][C_in][C_out] filter.
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct".
 #include <hip/hip_runtime.h>
 
@@ -44,6 +45,19 @@ conv_gather_kernel(ConvGeom g, const typename TR::T *__restrict__ x, const typen
     int e_lo, e_hi;
     fc_band_window(g, n0, n0 + 32, 1, &e_lo, &e_hi);
 
+    // Filter entry w'[kh][e - e_min][my_n].  With compact storage `we` is the original filter
+    // [KH][KW*C_in][C_out] and the entry is tap row t = e - (g-p)*C_in of output slot g, zero
+    // outside [0, KW*C_in) (paper: Eq. "filter_construct", gather form).
+    const int slot = (valid_n ? my_n : 0) / g.Co, co = (valid_n ? my_n : 0) - slot * g.Co;
+    const int t_off = (slot - g.pad_w) * g.C, taps_c = g.KW * g.C;
+    auto filt = [&](int kh, int e) -> T {
+        if (g.compact) {
+            const int tr = e - t_off;
+            return (tr >= 0 && tr < taps_c) ? we[((long long)kh * taps_c + tr) * g.Co + co] : (T)0.0f;
+        }
+        return we[((long long)kh * g.kwin + (e - g.e_min)) * g.NCo + my_n];
+    };
+
     floatx16_t acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
@@ -52,7 +66,6 @@ conv_gather_kernel(ConvGeom g, const typename TR::T *__restrict__ x, const typen
         const int hi = ho + kh - g.pad_h;
         const bool row_ok = valid_m && hi >= 0 && hi < g.H;
         const T *xrow = x + (img * g.H + (row_ok ? hi : 0)) * (long long)g.in_row;
-        const T *wrow = we + (long long)kh * g.kwin * g.NCo;
         const int col0 = wo * g.FC;
         for (int e0 = e_lo; e0 < e_hi; e0 += KS) {
             typename TR::Vec a, b;
@@ -60,7 +73,7 @@ conv_gather_kernel(ConvGeom g, const typename TR::T *__restrict__ x, const typen
                 const int e = e0 + hf;
                 const bool ek = e < e_hi;
                 const int col = col0 + e;
-                a = (valid_n && ek) ? wrow[(long long)(e - g.e_min) * g.NCo + my_n] : 0.0f;
+                a = (valid_n && ek) ? filt(kh, e) : 0.0f;
                 b = (row_ok && ek && col >= 0 && col < g.in_row) ? xrow[col] : 0.0f;
             } else {
 #pragma unroll
@@ -68,7 +81,7 @@ conv_gather_kernel(ConvGeom g, const typename TR::T *__restrict__ x, const typen
                     const int e = e0 + hf * PL + j;
                     const bool ek = e < e_hi;
                     const int col = col0 + e;
-                    a[j] = (valid_n && ek) ? wrow[(long long)(e - g.e_min) * g.NCo + my_n] : (T)0.0f;
+                    a[j] = (valid_n && ek) ? filt(kh, e) : (T)0.0f;
                     b[j] = (row_ok && ek && col >= 0 && col < g.in_row) ? xrow[col] : (T)0.0f;
                 }
             }

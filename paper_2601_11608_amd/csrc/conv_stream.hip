@@ -128,8 +128,12 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 const int e = e0 + 16 * ks;
                 const int n = n_lo + 32 * nt + r;
                 u32x4 v = {0u, 0u, 0u, 0u};
-                if (kh < KH && ks < KS && e < e_hi && n < g.NCo)
-                    v = wp[((long long)kh * q_per_kh + ((e - g.e_min) >> 3)) * g.NCo + n];
+                if (kh < KH && ks < KS && e < e_hi && n < g.NCo) {
+                    const int q = (e - g.e_min) >> 3;
+                    const long long ci = g.compact ? fc_compact_chunk(g, kh, q, n)
+                                                   : ((long long)kh * q_per_kh + q) * g.NCo + n;
+                    if (ci >= 0) v = wp[ci];  // off-band chunks of the compact form are zeros
+                }
                 wf[kh][ks][nt] = __builtin_bit_cast(Vec, v);
             }
     // bias enters as a rank-1 MFMA: A = bias in K slot 0, B = 1 in K slot 0

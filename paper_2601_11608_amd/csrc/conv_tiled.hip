@@ -124,14 +124,30 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
     }
     // filter: BN columns x QPB planes = NF chunks per thread, column-contiguous across threads
-    int nf[NF], qf[NF];
+    // The chunk for window chunk q of a column sits at  fbase + (kh*f_jmax + (q - fj0)) * f_stride
+    // when 0 <= q - fj0 < f_jmax.  Packed w': one run of q_per_kh chunks per kh, column stride NCo.
+    // Compact storage: the column's slot fixes the phase copy and the first window chunk its tap
+    // matrix reaches (fc_compact_chunk); chunks outside are structural zeros.
+    int nf[NF], qf[NF], fbase[NF], fj0[NF];
     bool vn[NF];
+    const int f_jmax = g.compact ? g.cJ : q_per_kh;
+    const int f_stride = g.compact ? g.Co : g.NCo;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
         const int idx = t + 256 * i;
         nf[i] = idx % BN;
         qf[i] = idx / BN;
         vn[i] = n0 + nf[i] < g.NCo;
+        const int n = vn[i] ? n0 + nf[i] : 0;
+        if (g.compact) {
+            const int slot = n / g.Co, co = n - slot * g.Co;
+            const int a = (slot - g.pad_w) * g.C - g.e_min;
+            fj0[i] = a >> 3;
+            fbase[i] = ((a & 7) / g.cgcd) * g.KH * g.cJ * g.Co + co;
+        } else {
+            fj0[i] = 0;
+            fbase[i] = n;
+        }
     }
 
     // Two register sets: the loads of block i+2 are issued while block i is computed and are
@@ -160,9 +176,9 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
 #pragma unroll
         for (int i = 0; i < NF; ++i) {
             const int e = e0 + 8 * qf[i];
-            const bool ok = vn[i] && e < e_hi;
-            const unsigned row = (unsigned)(kh * q_per_kh + ((e - g.e_min) >> 3));
-            const unsigned off = ok ? 16u * (row * (unsigned)g.NCo + (unsigned)(n0 + nf[i])) : kOutOfRange;
+            const int j = ((e - g.e_min) >> 3) - fj0[i];
+            const bool ok = vn[i] && e < e_hi && j >= 0 && j < f_jmax;
+            const unsigned off = ok ? 16u * ((unsigned)fbase[i] + (unsigned)(kh * f_jmax + j) * (unsigned)f_stride) : kOutOfRange;
             rf[i] = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
         }
         if (++kb_l == kblocks) {
@@ -296,7 +312,8 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
     a.total = (unsigned)total;
     a.per_xcd = (a.total + 7) / 8;
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
-    a.wp_bytes = (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
+    a.wp_bytes = g.compact ? (unsigned)((long long)fc_compact_phases(g) * g.KH * g.cJ * g.Co * 16)
+                           : (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
     const unsigned blocks = a.per_xcd * 8;
     if (g.relu)
         conv_tiled_kernel<TR, TN, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);

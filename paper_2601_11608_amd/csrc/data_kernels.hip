@@ -151,6 +151,35 @@ pack_filter_kernel(const uint16_t *__restrict__ we, u32x4 *__restrict__ pack, in
     }
 }
 
+// ---------------------------------------------------------------------------
+// Original filter -> compact MFMA operand storage (layout at fc_compact_chunk):
+// one thread per 16-byte chunk  cpk[ph][kh][j][co][0..7].  Only the non-zero
+// blocks of the expanded filter exist in this form
+// (paper: "Potential Optimizations for Sparsity", storing just the non-zero blocks).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kThreads)
+compact_filter_kernel(const uint16_t *__restrict__ w, u32x4 *__restrict__ cpk, int KH, int taps_c /* KW*C_in */,
+                      int Co, int cJ, int cgcd, long long total) {
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        const int co = (int)(i % Co);
+        long long r = i / Co;
+        const int j = (int)(r % cJ);
+        r /= cJ;
+        const int kh = (int)(r % KH);
+        const int ph = (int)(r / KH);
+        uint16_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int t = 8 * j + e - ph * cgcd;  // row of the kh-th KW*C_in x C_out tap matrix
+            v[e] = (t >= 0 && t < taps_c) ? w[((long long)kh * taps_c + t) * Co + co] : (uint16_t)0;
+        }
+        u32x4 out;
+        __builtin_memcpy(&out, v, 16);
+        cpk[i] = out;
+    }
+}
+
 inline int last_error() { return (int)hipGetLastError(); }
 
 }  // namespace
@@ -243,5 +272,15 @@ int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w
     const long long total = (long long)g.KH * (g.kwin / 8) * g.NCo;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
     pack_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    return last_error();
+}
+
+int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_compact, void *stream) {
+    if (elem_bytes != 2 || g.FC % 8 != 0) return (int)hipErrorInvalidValue;
+    hipStream_t st = (hipStream_t)stream;
+    const long long total = (long long)fc_compact_phases(g) * g.KH * g.cJ * g.Co;
+    const unsigned grid = blocks_for(total, kThreads, 1 << 16);
+    compact_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH, g.KW * g.C, g.Co,
+                                                     g.cJ, g.cgcd, total);
     return last_error();
 }

@@ -37,6 +37,8 @@ struct ConvGeom {
     int in_row;        // elements per input row  (Wf*FC)
     int out_row;       // elements per stored output row (W_out*Co, or Wf_out*NCo when kept folded)
     int relu, band, has_bias;
+    int compact;       // the filter operand is the compact per-phase storage (see fc_compact_chunk)
+    int cJ, cgcd;      // compact storage: chunks per (phase, kh), and gcd(C_in, 8)
     long long M;       // N*Hout*Wf_out
 };
 
@@ -59,6 +61,25 @@ FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int 
     *e_lo = lo;
     *e_hi = hi;
 }
+
+// Compact storage of the expanded filter for the 16-bit vector kernels.  Every output slot g
+// uses the same KW*C_in x C_out matrix per kh (the non-zero blocks of w' are copies of the original
+// taps; paper: "Potential Optimizations for Sparsity": keep only the non-zero blocks); slots differ
+// only in where that matrix starts, a = (g-p)*C_in - e_min rows into the window.  In 16-byte
+// chunks of 8 rows the start falls on phase a mod 8, a multiple of gcd(C_in, 8), so one
+// zero-padded copy per phase serves every slot:
+//   cpk[ph][kh][j][co][i] = w[kh][t / C_in][t % C_in][co],  t = 8*j + i - ph*gcd,  0 <= t < KW*C_in, else 0.
+// Returns the chunk of cpk that equals rows [e_min+8q, e_min+8q+8) of column n of w', or -1 when
+// those rows are structural zeros.
+FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
+    const int slot = n / g.Co, co = n - slot * g.Co;
+    const int a = (slot - g.pad_w) * g.C - g.e_min;  // >= 0 because e_min <= -p*C_in
+    const int j = q - (a >> 3);
+    if (j < 0 || j >= g.cJ) return -1;
+    return ((long long)(((a & 7) / g.cgcd) * g.KH + kh) * g.cJ + j) * g.Co + co;
+}
+FC_HD int fc_gcd8(int c) { return (c % 8 == 0) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
+FC_HD int fc_compact_phases(const ConvGeom &g) { return 8 / g.cgcd; }
 
 enum { FC_KERNEL_GATHER = 0, FC_KERNEL_TILED = 1, FC_KERNEL_STREAM = 2 };
 

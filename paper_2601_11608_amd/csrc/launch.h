@@ -29,6 +29,7 @@ int fc_launch_unfold(const foldconv_plan_s *p, const void *y_fold, void *y, void
 int fc_launch_pad_input(const foldconv_plan_s *p, const void *x, void *x_pad, void *stream);
 int fc_launch_pad_filter(const foldconv_plan_s *p, const void *w, void *w_pad, void *stream);
 int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream);
+int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_compact, void *stream);
 int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp,
                    const void *w_pack, const void *bias, void *y, void *stream);
 

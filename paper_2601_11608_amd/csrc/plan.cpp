@@ -100,6 +100,8 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     g.pad_h = pad_h; g.pad_w = pad_w;
     g.e_min = (int)(d_min * FC); g.e_max = (int)((d_max + 1) * FC); g.kwin = g.e_max - g.e_min;
     g.in_row = (int)(Wf * FC); g.out_row = (int)(W_out * C_out); g.M = M;
+    g.cgcd = fc_gcd8(C_in);
+    g.cJ = (8 - g.cgcd + KW * C_in + 7) / 8;
 
     // Zero-padded reference problem: F = 1, every pixel C_pad channels.
     ConvGeom &q = p->padc;
@@ -108,6 +110,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     q.pad_h = pad_h; q.pad_w = pad_w;
     q.e_min = -pad_w * C_pad; q.e_max = (KW - pad_w) * C_pad; q.kwin = q.e_max - q.e_min;
     q.in_row = W * C_pad; q.out_row = (int)(W_out * C_out); q.M = M_pad;
+    q.cgcd = 8; q.cJ = KW * C_pad / 8;
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
     s.padded_kernel = fc_choose_kernel(q, dtype);
@@ -115,6 +118,11 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     const long long xpad_bytes = (long long)N * H * W * C_pad * eb;
     const long long wpad_bytes = (long long)KH * KW * C_pad * C_out * eb;
     s.workspace_bytes = s.conv_kernel == FC_KERNEL_GATHER ? 0 : (long long)align_up((size_t)s.w_exp_bytes, 256);
+    // Compact filter: one zero-padded copy of the KW*C_in x C_out tap matrix per kh and per chunk
+    // phase for the vector kernels; the gather kernel reads the original filter as it is.
+    s.filter_compact_bytes = (long long)align_up(
+        s.conv_kernel == FC_KERNEL_GATHER ? (size_t)s.w_bytes
+                                          : (size_t)fc_compact_phases(g) * KH * g.cJ * C_out * 16, 256);
     p->ws_xpad = 0;
     p->ws_wpad = align_up((size_t)xpad_bytes, 256);
     p->ws_wpack = p->ws_wpad + align_up((size_t)wpad_bytes, 256);
@@ -140,10 +148,14 @@ extern "C" int foldconv_plan_gemm(long long M, int K, int N, int fold_factor, fo
     if (M % fold_factor != 0) return FOLDCONV_ERR_INDIVISIBLE;
     // paper, "GEMM as a 1x1 Convolution": rows of A are spatial positions with K channels.  A 1x1
     // kernel couples no two positions, so the M rows may be laid out as any H x W image; the
-    // synthetic width is taken as F times the largest divisor of M/F up to 16384, which keeps
-    // image rows short enough for the vector kernels' row arithmetic.
+    // synthetic width is taken as F times the largest divisor of M/F that keeps the unfolded
+    // width under 65000 pixels (and the folded one at most 16384), short enough for the vector
+    // kernels' row arithmetic in the folded and in the zero-padded problem alike.
     const long long Mf = M / fold_factor;
-    long long d = Mf < 16384 ? Mf : 16384;
+    long long cap = 64999 / fold_factor;
+    if (cap > 16384) cap = 16384;
+    if (cap < 1) cap = 1;
+    long long d = Mf < cap ? Mf : cap;
     while (Mf % d != 0) --d;
     return foldconv_plan(1, (int)(Mf / d), (int)(d * fold_factor), K, N, 1, 1, 0, fold_factor, dtype, out);
 }

@@ -22,6 +22,7 @@ class FoldedLayer:
         fc.foldconv_pack_filter(self.plan, self.w_exp, self.ws)
         self.ws_pad = None
         self.pad_ready = False
+        self.ws_compact = None
 
     def out_shape(self):
         s = self.plan.shapes
@@ -30,11 +31,19 @@ class FoldedLayer:
     def new_output(self):
         return torch.empty(self.out_shape(), dtype=self.dtype, device=self.w.device)
 
-    def forward(self, x, y, flags=0, repack=False):
-        """fold (aliased: x' shares x's bytes) + folded convolution + fused reconstruct."""
+    def forward(self, x, y, flags=0, repack=False, compact=False):
+        """fold (aliased: x' shares x's bytes) + folded convolution + fused reconstruct.
+        compact=True runs from the compact filter (non-zero blocks only), built once from w."""
         fc.foldconv_fold_input(self.plan, x, x)
         if self.layer.relu:
             flags |= fc.FLAG_RELU
+        if compact:
+            if self.ws_compact is None:
+                n = max(int(self.plan.shapes.filter_compact_bytes), 256)
+                self.ws_compact = torch.empty(n, dtype=torch.uint8, device=self.w.device)
+                fc.foldconv_pack_filter_compact(self.plan, self.w, self.ws_compact)
+            fc.foldconv_forward(self.plan, x, None, self.b, y, self.ws_compact, flags | fc.FLAG_FILTER_COMPACT)
+            return y
         if not repack:
             flags |= fc.FLAG_FILTER_PACKED
         fc.foldconv_forward(self.plan, x, self.w_exp, self.b, y, self.ws, flags)
@@ -59,12 +68,12 @@ class FoldedStack:
         self.layers = [FoldedLayer(l, w, b, device) for l, w, b in zip(layers, ws, bs)]
         self.outs = [l.new_output() for l in self.layers]
 
-    def forward(self, x, flags=0, padded=False):
+    def forward(self, x, flags=0, padded=False, compact=False):
         a = x
         for l, y in zip(self.layers, self.outs):
             if padded:
                 l.forward_padded(a, y)
             else:
-                l.forward(a, y, flags)
+                l.forward(a, y, flags, compact=compact)
             a = y
         return a

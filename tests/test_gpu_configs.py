@@ -35,7 +35,7 @@ CASES = [("c1", None), ("c2", [0, 17, 63]), ("c3", None), ("c4", None), ("c5", [
 
 
 @pytest.mark.parametrize("name,images", CASES)
-@pytest.mark.parametrize("mode", ["band", "dense", "padded"])
+@pytest.mark.parametrize("mode", ["band", "dense", "padded", "compact"])
 def test_config_matches_oracle(env, oracle, name, images, mode):
     fc, runner, wl = env
     if mode == "dense" and name == "c5":
@@ -47,7 +47,8 @@ def test_config_matches_oracle(env, oracle, name, images, mode):
     for y in stack.outs:
         y.fill_(float("nan"))
     xd = x.cuda()
-    y = stack.forward(xd, flags=(fc.FLAG_DENSE_K if mode == "dense" else 0), padded=(mode == "padded"))
+    y = stack.forward(xd, flags=(fc.FLAG_DENSE_K if mode == "dense" else 0), padded=(mode == "padded"),
+                      compact=(mode == "compact"))
     torch.cuda.synchronize()
     assert not bool(torch.isnan(y).any()), "unwritten output elements"
     ref = oracle_images(oracle, layers, x, ws, bs, images)

@@ -136,6 +136,80 @@ def test_expand_filter_bit_exact(fc, oracle, KH, KW, C, Co, F, pad, dt):
     assert np.array_equal(bits_as_f64(w_exp), want)
 
 
+def run_compact(fc, plan, x, w, b, flags=0):
+    """compact filter straight from w (no expanded filter anywhere) -> forward; returns y (CPU tensor)."""
+    s = plan.shapes
+    ws = torch.full((max(int(s.filter_compact_bytes), 256),), 0xFF, dtype=torch.uint8, device="cuda")
+    fc.foldconv_pack_filter_compact(plan, dev(w), ws)
+    if flags & fc.FLAG_KEEP_FOLDED:
+        y = torch.full((s.N, s.H_out, s.W_out_fold, s.Co_fold), float("nan"), dtype=x.dtype, device="cuda")
+    else:
+        y = torch.full((s.N, s.H_out, s.W_out, s.C_out), float("nan"), dtype=x.dtype, device="cuda")
+    fc.foldconv_forward(plan, dev(x), None, dev(b), y, ws, flags | fc.FLAG_FILTER_COMPACT)
+    torch.cuda.synchronize()
+    return y.cpu()
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: "x".join(map(str, c[:9])))
+def test_forward_compact_filter(fc, oracle, case, dt):
+    """Only the non-zero blocks of w' are stored; the same values reach the same MFMA slots, so
+    the result equals the packed-w' route bit for bit, and the oracle within tolerance."""
+    N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
+    x = draw((N, H, W, C), dt, 1)
+    w = (draw((KH, KW, C, Co), dt, 2) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+    b = draw((Co,), dt, 3) if hb else None
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    ref = oracle.conv_direct(f64(x), f64(w), None if b is None else f64(b), ph, pw, relu)
+    plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, x.dtype)
+    rflag = fc.FLAG_RELU if relu else 0
+    for extra in (0, fc.FLAG_DENSE_K, fc.FLAG_KEEP_FOLDED):
+        y_c = run_compact(fc, plan, x, w, b, rflag | extra)
+        y_p = run_folded(fc, plan, x, w, b, rflag | extra)
+        assert np.array_equal(bits(y_c), bits(y_p)), extra
+        if not extra:
+            assert rel_l2_per_image(f64(y_c), ref) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("KH,KW,C,Co,F,pad", [(3, 3, 3, 64, 16, 1), (1, 9, 1, 64, 32, 4), (5, 1, 1, 1, 8, 0),
+                                               (3, 3, 12, 48, 4, 1), (2, 4, 2, 8, 4, 2), (3, 3, 132, 256, 4, 1),
+                                               (3, 3, 20, 36, 4, 1), (1, 1, 5, 7, 8, 0), (3, 5, 6, 10, 4, 2)])
+def test_compact_filter_holds_the_band_of_the_expanded_filter(fc, oracle, KH, KW, C, Co, F, pad, dt):
+    """Every 8-row chunk of every column of the oracle's expanded filter is either all zero or
+    found, bit for bit, where the compact layout says it is; the compact form is much smaller."""
+    w = draw((KH, KW, C, Co), dt, 12)
+    plan = fc.foldconv_plan(1, 8, 8 * F, C, Co, KH, KW, pad, F, w.dtype)
+    s = plan.shapes
+    assert s.conv_kernel != 0                    # a vector kernel: chunked compact storage
+    ws = torch.full((int(s.filter_compact_bytes),), 0xFF, dtype=torch.uint8, device="cuda")
+    fc.foldconv_pack_filter_compact(plan, w.cuda(), ws)
+    torch.cuda.synchronize()
+    g8 = int(np.gcd(C, 8))
+    P, cJ = 8 // g8, (8 - g8 + KW * C + 7) // 8
+    assert s.filter_compact_bytes == -(-P * KH * cJ * Co * 16 // 256) * 256
+    cpk = ws.cpu().numpy().view(np.int16)[: P * KH * cJ * Co * 8].reshape(P, KH, cJ, Co, 8)
+    w_exp = oracle.expand_filter(bits_as_f64(w), F, s.pad_w).astype(np.int16)        # [KH, KW', FC, FCo] bit patterns
+    w_exp = w_exp.reshape(KH, s.KW_fold * F * C, F * Co)
+    e_min = s.d_min * F * C
+    used = np.zeros((P, KH, cJ, Co), dtype=bool)
+    for g in range(F):
+        a = (g - s.pad_w) * C - e_min
+        assert a >= 0
+        for q in range(w_exp.shape[1] // 8):
+            rows = w_exp[:, 8 * q:8 * q + 8, g * Co:(g + 1) * Co]                      # [KH, 8, Co]
+            j = q - (a >> 3)
+            if 0 <= j < cJ:
+                assert np.array_equal(cpk[(a & 7) // g8, :, j].transpose(0, 2, 1), rows), (g, q)
+                used[(a & 7) // g8, :, j] = True
+            else:
+                assert not rows.any(), (g, q)
+    if F >= P:                                   # every phase copy serves some slot: what no slot reads is padding
+        assert not cpk[~used].any()
+    if s.w_exp_bytes >= 4096:                    # beyond the 16-byte chunk and 256-byte rounding effects
+        assert s.filter_compact_bytes < s.w_exp_bytes
+
+
 @pytest.mark.parametrize("dt", ["f16", "f32"])
 @pytest.mark.parametrize("N,H,W,C,F", [(2, 5, 48, 3, 16), (1, 1, 16000, 1, 32), (3, 7, 20, 5, 4), (1, 3, 6, 1, 2)])
 def test_fold_input_bit_exact(fc, oracle, N, H, W, C, F, dt):

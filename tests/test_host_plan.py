@@ -2,6 +2,7 @@
 every declared symbol, the plan's closed forms agree with the oracle's (which
 are pinned by enumeration), error paths, and struct layout."""
 import ctypes
+import math
 import os
 import re
 import subprocess
@@ -145,8 +146,33 @@ def test_null_pointer_calls_are_rejected_without_gpu(fc):
     assert lib.conv_padded_forward(h, None, None, None, None, None, 0, 0, None) == -1
     assert lib.foldconv_forward(h, 256, 512, None, 1024, None, 0, 1 << 20, None) == -1     # unknown flag
     assert lib.conv_padded_forward(h, 256, 512, None, 1024, None, 0, 0, None) == -4        # workspace missing
+    assert lib.foldconv_pack_filter_compact(h, None, 256, 1 << 20, None) == -1
+    assert lib.foldconv_pack_filter_compact(h, 512, None, 0, None) == -4                   # workspace missing
+    assert lib.foldconv_forward(h, 256, None, None, 1024, None, 0, 16, None) == -4         # compact filter missing
+    assert lib.foldconv_forward(h, 256, None, None, 1024, None, 0, 0, None) == -1          # no filter at all
     assert lib.foldconv_fold_input(h, 4096, 4096, None) == 0                               # alias: nothing to do
     assert lib.foldconv_fold_input(h, 4096, 4096 + 16, None) == -1                         # partial overlap
+
+
+def test_compact_filter_size(fc):
+    """Compact storage keeps 8/gcd(C_in,8) zero-padded copies of the KW*C_in x C_out tap matrix per
+    kh in 16-byte chunks of 8 rows: close to KW/(KW'*F) of the expanded filter (the density of the
+    paper's block structure) once rounding to chunks is small."""
+    from paper_2601_11608_amd import workloads as wl
+
+    for name in ("c2", "c3", "c4", "c5"):
+        for l in wl.CONFIGS[name]:
+            s = fc.foldconv_plan(*l.plan_args(), wl.DTYPES[l.dtype]).shapes
+            g8 = math.gcd(l.C_in, 8)
+            chunks = (8 - g8 + l.KW * l.C_in + 7) // 8
+            want = (8 // g8) * l.KH * chunks * l.C_out * 16
+            assert s.filter_compact_bytes == (want + 255) // 256 * 256
+            assert s.filter_compact_bytes < s.w_exp_bytes / 3
+    s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
+    assert (s.w_exp_bytes, s.filter_compact_bytes) == (884736, 49152)
+    # the gather kernel (fp32, or channels off the chunk alignment) reads the original filter itself
+    s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 8, "float32").shapes
+    assert s.conv_kernel == 0 and s.filter_compact_bytes == (s.w_bytes + 255) // 256 * 256
 
 
 def test_workloads_shapes():
@@ -170,7 +196,8 @@ def test_gemm_plan_is_a_folded_one_by_one_conv(fc):
     assert (s.C_fold, s.Co_fold) == (48, 256) and s.unfold_is_alias == 1
     assert s.useful_flops == 2.0 * (1 << 20) * 12 * 64
     assert s.x_bytes == (1 << 20) * 12 * 2 and s.y_bytes == (1 << 20) * 64 * 2
-    assert s.W_out_fold < 65000            # rows short enough for the vector kernels
+    assert s.W_out_fold < 65000 and s.W_out < 65000   # rows short enough for the vector kernels, folded or not
+    assert s.padded_kernel == 2            # so the zero-padded reference streams as well
     with pytest.raises(fc.FoldconvError) as e:
         fc.foldconv_plan_gemm(1001, 12, 64, 4, "float16")
     assert e.value.status == -2
