@@ -194,3 +194,101 @@ void oracle_pad_channels(const double *x, double *xp, size_t pixels, int C, int 
     for (size_t i = 0; i < pixels; ++i)
         for (int c = 0; c < C_pad; ++c) xp[i * C_pad + c] = (c < C) ? x[i * C + c] : 0.0;
 }
+
+/* ------------------------------------------------------------------------
+ * Height folding for channels-first tensors (paper: Introduction, "width
+ * folding for input in NHWC format (alternatively height folding for NCHW
+ * format)").  The same rewrite with the roles of H and W exchanged:
+ *   x   [N][C][H][W]            input, NCHW
+ *   w   [Co][C][KH][KW]         filter, OIHW
+ *   xh  [N][F*C][H/F][W]        height-folded input,  xh[n,f*C+c,h',w] = x[n,c,F*h'+f,w]
+ *   wh  [F*Co][F*C][KHf][KW]    expanded filter,
+ *         wh[g*Co+co, f*C+c, d-d_min, kw] = w[co,c,F*d+f-g+p,kw]  (tap index in [0,KH), else 0)
+ *   yh  [N][F*Co][H'_out][W_out]   folded output, yh[n,g*Co+co,h',w] = y[n,co,F*h'+g,w]
+ * The closed forms (d_min, d_max, KHf, pads) are oracle_folded_shapes() with
+ * H, KH in the places of W, KW.
+ * ------------------------------------------------------------------------ */
+
+/* Direct cross-correlation on channels-first tensors, stride 1, zero padding
+ * by omitting out-of-range taps; output extent given by the caller (as in
+ * oracle_conv2d_nhwc) so it also serves the asymmetric height padding of the
+ * folded problem.  Fixed (c, kh, kw) summation order per output. */
+void oracle_conv2d_nchw(const double *x, const double *w, const double *b, double *y,
+                        int N, int C, int H, int W, int Co, int KH, int KW,
+                        int pad_top, int pad_left, int H_out, int W_out, int relu)
+{
+    long planes = (long)N * Co;
+#pragma omp parallel for schedule(static)
+    for (long q = 0; q < planes; ++q) {
+        int n = (int)(q / Co), co = (int)(q % Co);
+        for (int ho = 0; ho < H_out; ++ho)
+            for (int wo = 0; wo < W_out; ++wo) {
+                double acc = b ? b[co] : 0.0;
+                for (int c = 0; c < C; ++c)
+                    for (int kh = 0; kh < KH; ++kh) {
+                        int hi = ho + kh - pad_top;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int kw = 0; kw < KW; ++kw) {
+                            int wi = wo + kw - pad_left;
+                            if (wi < 0 || wi >= W) continue;
+                            acc += x[(((size_t)n * C + c) * H + hi) * W + wi] *
+                                   w[(((size_t)co * C + c) * KH + kh) * KW + kw];
+                        }
+                    }
+                if (relu && acc < 0.0) acc = 0.0;
+                y[(((size_t)n * Co + co) * H_out + ho) * W_out + wo] = acc;
+            }
+    }
+}
+
+/* xh[n,f*C+c,h',w] = x[n,c,F*h'+f,w]: whole rows of W elements move. */
+void oracle_fold_input_h_nchw(const double *x, double *xh, int N, int C, int H, int W, int F)
+{
+    int Hf = H / F;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int hp = 0; hp < Hf; ++hp)
+                for (int f = 0; f < F; ++f)
+                    for (int wi = 0; wi < W; ++wi)
+                        xh[(((size_t)n * F * C + (size_t)f * C + c) * Hf + hp) * W + wi] =
+                            x[(((size_t)n * C + c) * H + (F * hp + f)) * W + wi];
+}
+
+/* Zeros, then each original (co, c) tap column copied to its place: output
+ * slot g, tap kh lands in folded tap d, input block f with g + kh - p = F*d + f. */
+void oracle_expand_filter_h_oihw(const double *w, double *wh, int Co, int C, int KH, int KW,
+                                 int F, int p)
+{
+    int sh[8];
+    oracle_folded_shapes(F, KH, p, F, sh);
+    int d_min = sh[1], KHf = sh[3];
+    size_t FC = (size_t)F * C;
+    memset(wh, 0, sizeof(double) * (size_t)F * Co * FC * KHf * KW);
+    for (int g = 0; g < F; ++g)
+        for (int kh = 0; kh < KH; ++kh) {
+            long t = (long)g + kh - p;
+            long d = floor_div(t, F);
+            long f = t - d * F;
+            for (int co = 0; co < Co; ++co)
+                for (int c = 0; c < C; ++c)
+                    for (int kw = 0; kw < KW; ++kw)
+                        wh[((((size_t)g * Co + co) * FC + (size_t)f * C + c) * KHf + (size_t)(d - d_min)) * KW + kw] =
+                            w[(((size_t)co * C + c) * KH + kh) * KW + kw];
+        }
+}
+
+/* y[n,co,F*h'+g,w] = yh[n,g*Co+co,h',w] for F*h'+g < H_out. */
+void oracle_unfold_output_h_nchw(const double *yh, double *y, int N, int Co, int Hf_out, int W_out,
+                                 int F, int H_out)
+{
+    for (int n = 0; n < N; ++n)
+        for (int g = 0; g < F; ++g)
+            for (int co = 0; co < Co; ++co)
+                for (int hp = 0; hp < Hf_out; ++hp) {
+                    int ho = F * hp + g;
+                    if (ho >= H_out) continue;
+                    for (int wi = 0; wi < W_out; ++wi)
+                        y[(((size_t)n * Co + co) * H_out + ho) * W_out + wi] =
+                            yh[(((size_t)n * F * Co + (size_t)g * Co + co) * Hf_out + hp) * W_out + wi];
+                }
+}

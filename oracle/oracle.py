@@ -54,6 +54,14 @@ def _load():
         lib.oracle_unfold_output.restype = None
         lib.oracle_pad_channels.argtypes = [_D, _D, ctypes.c_size_t, _I, _I]
         lib.oracle_pad_channels.restype = None
+        lib.oracle_conv2d_nchw.argtypes = [_D, _D, _D, _D] + [_I] * 12
+        lib.oracle_conv2d_nchw.restype = None
+        lib.oracle_fold_input_h_nchw.argtypes = [_D, _D] + [_I] * 5
+        lib.oracle_fold_input_h_nchw.restype = None
+        lib.oracle_expand_filter_h_oihw.argtypes = [_D, _D] + [_I] * 6
+        lib.oracle_expand_filter_h_oihw.restype = None
+        lib.oracle_unfold_output_h_nchw.argtypes = [_D, _D] + [_I] * 6
+        lib.oracle_unfold_output_h_nchw.restype = None
         _lib = lib
     return _lib
 
@@ -179,3 +187,75 @@ def conv_stack(x, ws, pad, relu_between=True):
         ph, pw = axis_pads(w.shape[0], w.shape[1], pad)
         a = conv_direct(a, w, None, ph, pw, relu=(relu_between and i + 1 < len(ws)))
     return a
+
+
+# --- channels-first tensors and height folding ---------------------------------
+# paper: Introduction, "width folding for input in NHWC format (alternatively
+# height folding for NCHW format)".  x[N,C,H,W], w[Co,C,KH,KW] (OIHW).
+
+def conv2d_general_nchw(x, w, b, pad_top, pad_left, H_out, W_out, relu=False):
+    x, w = _f64(x), _f64(w)
+    N, C, H, W = x.shape
+    Co, C2, KH, KW = w.shape
+    assert C2 == C
+    bb = None if b is None else _f64(b)
+    y = np.empty((N, Co, H_out, W_out), dtype=np.float64)
+    _load().oracle_conv2d_nchw(
+        _p(x), _p(w), None if bb is None else _p(bb), _p(y),
+        N, C, H, W, Co, KH, KW, pad_top, pad_left, H_out, W_out, int(bool(relu)),
+    )
+    return y
+
+
+def conv_direct_nchw(x, w, b=None, pad_h=0, pad_w=0, relu=False):
+    """The definition on channels-first tensors (stride 1, symmetric zero padding)."""
+    N, C, H, W = x.shape
+    KH, KW = w.shape[2], w.shape[3]
+    return conv2d_general_nchw(x, w, b, pad_h, pad_w, H + 2 * pad_h - KH + 1, W + 2 * pad_w - KW + 1, relu)
+
+
+def fold_input_h_nchw(x, F):
+    """xh[n, f*C+c, h', w] = x[n, c, F*h'+f, w]."""
+    x = _f64(x)
+    N, C, H, W = x.shape
+    assert H % F == 0, "guard: H mod F != 0"
+    xh = np.empty((N, F * C, H // F, W), dtype=np.float64)
+    _load().oracle_fold_input_h_nchw(_p(x), _p(xh), N, C, H, W, F)
+    return xh
+
+
+def expand_filter_h_oihw(w, F, p):
+    """wh[g*Co+co, f*C+c, d-d_min, kw] = w[co, c, F*d+f-g+p, kw] (zero outside the tap range)."""
+    w = _f64(w)
+    Co, C, KH, KW = w.shape
+    sh = folded_shapes(F, KH, p, F)
+    wh = np.empty((F * Co, F * C, sh["KWf"], KW), dtype=np.float64)
+    _load().oracle_expand_filter_h_oihw(_p(w), _p(wh), Co, C, KH, KW, F, p)
+    return wh
+
+
+def unfold_output_h_nchw(yh, F, Co, H_out):
+    """y[n, co, F*h'+g, w] = yh[n, g*Co+co, h', w] for F*h'+g < H_out."""
+    yh = _f64(yh)
+    N, FCo, Hf_out, W_out = yh.shape
+    assert FCo == F * Co
+    y = np.empty((N, Co, H_out, W_out), dtype=np.float64)
+    _load().oracle_unfold_output_h_nchw(_p(yh), _p(y), N, Co, Hf_out, W_out, F, H_out)
+    return y
+
+
+def conv_rewrite_h_nchw(x, w, b=None, pad_h=0, pad_w=0, F=1, relu=False, return_parts=False):
+    """Height-folding rewrite on the CPU: fold H into channels, expand the filter along KH,
+    replicate the bias, ordinary channels-first convolution on the folded shapes, reconstruct."""
+    N, C, H, W = x.shape
+    Co, _, KH, KW = w.shape
+    sh = folded_shapes(H, KH, pad_h, F)          # the closed forms with H, KH in place of W, KW
+    xh = fold_input_h_nchw(x, F)
+    wh = expand_filter_h_oihw(w, F, pad_h)
+    bf = None if b is None else tile_bias(b, F)
+    W_out = W + 2 * pad_w - KW + 1
+    yh = conv2d_general_nchw(xh, wh, bf, sh["pad_left_f"], pad_w, sh["Wf_out"], W_out, relu)
+    y = unfold_output_h_nchw(yh, F, Co, sh["W_out"])
+    if return_parts:
+        return y, dict(xh=xh, wh=wh, bf=bf, yh=yh, shapes=sh)
+    return y
