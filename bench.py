@@ -224,6 +224,36 @@ def main():
                               "useful_tflops": gs.useful_flops / (g_ms * 1e-3) / 1e12,
                               "GBps": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9,
                               "frac_of_hbm_peak": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        # the headline layer handed over channels-first (NCHW / OIHW): fold and reconstruct are real
+        # re-indexing kernels here, the convolution between them is the same kernel as above
+        xn = x.permute(0, 3, 1, 2).contiguous().cuda()
+        wn = ws[0].permute(3, 2, 0, 1).contiguous().cuda()
+        nchw = {}
+        for axis_name, axis in (("fold_w", fc.FOLD_W), ("fold_h", fc.FOLD_H)):
+            l = layer
+            pn = fc.foldconv_plan_nchw(l.N, l.C_in, l.H, l.W, l.C_out, l.KH, l.KW, l.pad, l.F, axis, xn.dtype)
+            sn = pn.shapes
+            w_exp_n = torch.empty(sn.w_exp_bytes // sn.elem_bytes, dtype=xn.dtype, device="cuda")
+            fc.foldconv_expand_filter_oihw(pn, wn, w_exp_n)
+            ws_n = torch.empty(max(int(sn.workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+            fc.foldconv_pack_filter(pn, w_exp_n, ws_n)
+            xf_n = torch.empty_like(xn)
+            yn = torch.empty(y.numel(), dtype=xn.dtype, device="cuda")
+            bn = L.b
+
+            def step_nchw():
+                fc.foldconv_fold_input_nchw(pn, xn, xf_n)
+                fc.foldconv_forward(pn, xf_n, w_exp_n, bn, y, ws_n, fc.FLAG_KEEP_FOLDED | fc.FLAG_FILTER_PACKED)
+                fc.foldconv_unfold_output_nchw(pn, y, yn)
+
+            _, n_ms = time_events(step_nchw, 10, 2)
+            _, nf_ms = time_events(lambda: fc.foldconv_fold_input_nchw(pn, xn, xf_n), 20, 3)
+            _, nu_ms = time_events(lambda: fc.foldconv_unfold_output_nchw(pn, y, yn), 10, 2)
+            nchw[axis_name] = {"total_ms": n_ms, "fold_ms": nf_ms, "unfold_ms": nu_ms,
+                               "unfold_GBps": 2 * sn.y_bytes / (nu_ms * 1e-3) / 1e9,
+                               "useful_tflops": sn.useful_flops / (n_ms * 1e-3) / 1e12}
+            del w_exp_n, ws_n, xf_n, yn
+        extras["nchw"] = nchw
         out["extras"] = extras
 
     if not args.no_cpu_baseline:

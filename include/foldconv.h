@@ -71,6 +71,9 @@ enum {
                                          of w'); w_exp is not read and may be NULL              */
 };
 
+/* Which image axis of a channels-first (NCHW) tensor is folded into the channels. */
+enum { FOLDCONV_FOLD_W = 0, FOLDCONV_FOLD_H = 1 };
+
 /* Everything a caller needs to size buffers and to report throughput. */
 typedef struct foldconv_shapes_s {
     int32_t N, H, W, C_in, C_out, KH, KW, pad, F, dtype;
@@ -87,6 +90,9 @@ typedef struct foldconv_shapes_s {
     int32_t conv_kernel;            /* 0 = gather MFMA, 1 = LDS-tiled MFMA, 2 = streaming MFMA
                                        (which kernel foldconv_forward will launch)            */
     int32_t padded_kernel;          /* same, for conv_padded_forward                          */
+    int32_t fold_axis;              /* FOLDCONV_FOLD_W; FOLDCONV_FOLD_H for a plan made by
+                                       foldconv_plan_nchw with height folding: then H, W, KH, KW
+                                       and the *_out fields above describe the transposed image */
     int64_t gemm_M, gemm_N, gemm_K; /* implicit GEMM of the folded problem, dense K           */
     int64_t x_bytes, w_bytes, bias_bytes, w_exp_bytes, y_bytes, y_fold_bytes;
     int64_t workspace_bytes;        /* for foldconv_forward / foldconv_pack_filter            */
@@ -121,6 +127,26 @@ FOLDCONV_API int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH,
  * paper: section "Generalization to GEMM via 1x1 Convolution".
  */
 FOLDCONV_API int foldconv_plan_gemm(long long M, int K, int N, int fold_factor, foldconv_dtype_t dtype,
+                                    foldconv_plan_t *out);
+
+/*
+ * Plan for channels-first tensors  x [N][C_in][H][W],  w [C_out][C_in][KH][KW]
+ * (OIHW),  y [N][C_out][H_out][W_out].  fold_axis = FOLDCONV_FOLD_H folds the
+ * image height into the channels (H must be divisible by F), FOLDCONV_FOLD_W
+ * the width.  Neither is an alias in this layout (no spatial axis is adjacent
+ * to the channel axis), so the fold and the reconstruct are real re-indexing
+ * kernels: foldconv_fold_input_nchw and foldconv_unfold_output_nchw, with
+ * foldconv_expand_filter_oihw for the filter.  The folded tensors are kept
+ * channels-last, x'[n][a][b'][f*C_in+c] with (a, F*b'+f) = (h, w) for
+ * FOLD_W and (w, h) for FOLD_H, so foldconv_forward (with
+ * FOLDCONV_FLAG_KEEP_FOLDED) and its kernels are the same as for NHWC; for
+ * FOLD_H the plan is the width-fold plan of the transposed image and
+ * shapes.{H,W,KH,KW,...} are reported in that transposed space.
+ * paper: Introduction, "width folding for input in NHWC format (alternatively
+ * height folding for NCHW format)".
+ */
+FOLDCONV_API int foldconv_plan_nchw(int N, int C_in, int H, int W, int C_out, int KH, int KW, int pad,
+                                    int fold_factor, int fold_axis, foldconv_dtype_t dtype,
                                     foldconv_plan_t *out);
 
 /*
@@ -167,6 +193,26 @@ FOLDCONV_API int foldconv_fold_input(foldconv_plan_t plan, const void *x, void *
  * when shapes.unfold_is_alias (then nothing is launched).
  */
 FOLDCONV_API int foldconv_unfold_output(foldconv_plan_t plan, const void *y_fold, void *y, void *stream);
+
+/*
+ * Channels-first counterparts of the three data-movement steps.  All are
+ * bit-exact moves; buffers must not overlap.
+ *   foldconv_expand_filter_oihw: w [C_out][C_in][KH][KW] -> w' in the same
+ *     canonical layout foldconv_expand_filter writes (Eq. "filter_construct"
+ *     with the plan's folded axis in the role of W).
+ *   foldconv_fold_input_nchw:  x [N][C_in][H][W] -> x' (shapes.x_bytes),
+ *     x'[n][a][b'][f*C_in+c] = x[n][c][h][w] with (h, w) = (a, F*b'+f) for
+ *     FOLD_W and (F*b'+f, a) for FOLD_H  (Eq. "width_fold_def" on that axis).
+ *   foldconv_unfold_output_nchw:  y' [N][H_out][W'_out][F*C_out] as written by
+ *     foldconv_forward with FOLDCONV_FLAG_KEEP_FOLDED (plan space; the same
+ *     bytes as the default output when shapes.unfold_is_alias)
+ *     -> y [N][C_out][H_out][W_out] of the image, dropping folded slots at or
+ *     beyond the output extent (Reconstruct step).
+ * A plan made by foldconv_plan is taken as FOLDCONV_FOLD_W.
+ */
+FOLDCONV_API int foldconv_expand_filter_oihw(foldconv_plan_t plan, const void *w_oihw, void *w_exp, void *stream);
+FOLDCONV_API int foldconv_fold_input_nchw(foldconv_plan_t plan, const void *x_nchw, void *x_fold, void *stream);
+FOLDCONV_API int foldconv_unfold_output_nchw(foldconv_plan_t plan, const void *y_fold, void *y_nchw, void *stream);
 
 /*
  * Re-order w' into the operand order of the MFMA kernels (8 consecutive K
@@ -216,7 +262,8 @@ FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, cons
  * from Channel Zero-Padding".  x and w are the ORIGINAL tensors; the padded
  * copies live in workspace (shapes.padded_workspace_bytes).  With
  * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again.
- * FOLDCONV_FLAG_KEEP_FOLDED and FOLDCONV_FLAG_DENSE_K are ignored.
+ * FOLDCONV_FLAG_KEEP_FOLDED, FOLDCONV_FLAG_DENSE_K and
+ * FOLDCONV_FLAG_FILTER_COMPACT are ignored.
  */
 FOLDCONV_API int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias,
                         void *y, void *workspace, size_t workspace_bytes, unsigned flags,

@@ -9,21 +9,27 @@ from .binding import (  # noqa: F401
     FLAG_FILTER_PACKED,
     FLAG_KEEP_FOLDED,
     FLAG_RELU,
+    FOLD_H,
+    FOLD_W,
     FoldconvError,
     Plan,
     conv_padded_forward,
     foldconv_expand_filter,
+    foldconv_expand_filter_oihw,
     foldconv_fold_input,
+    foldconv_fold_input_nchw,
     foldconv_forward,
     foldconv_pack_filter,
     foldconv_pack_filter_compact,
     foldconv_plan,
     foldconv_plan_gemm,
+    foldconv_plan_nchw,
     foldconv_choose_fold,
     foldconv_plan_destroy,
     foldconv_plan_query,
     foldconv_strerror,
     foldconv_unfold_output,
+    foldconv_unfold_output_nchw,
     library_path,
     load_library,
 )

@@ -16,6 +16,8 @@ FLAG_DENSE_K = 2
 FLAG_KEEP_FOLDED = 4
 FLAG_FILTER_PACKED = 8
 FLAG_FILTER_COMPACT = 16
+FOLD_W = 0
+FOLD_H = 1
 
 _DTYPE_CODE = {"float32": 0, "float16": 1, "bfloat16": 2}
 
@@ -34,7 +36,7 @@ class Shapes(ctypes.Structure):
             "N", "H", "W", "C_in", "C_out", "KH", "KW", "pad", "F", "dtype", "pad_h", "pad_w",
             "W_fold", "C_fold", "Co_fold", "d_min", "d_max", "KW_fold", "pad_left_fold", "pad_right_fold",
             "H_out", "W_out", "W_out_fold", "unfold_is_alias", "C_pad", "elem_bytes", "conv_kernel",
-            "padded_kernel")]
+            "padded_kernel", "fold_axis")]
         + [(n, ctypes.c_int64) for n in (
             "gemm_M", "gemm_N", "gemm_K", "x_bytes", "w_bytes", "bias_bytes", "w_exp_bytes", "y_bytes",
             "y_fold_bytes", "workspace_bytes", "padded_workspace_bytes", "filter_compact_bytes")]
@@ -70,6 +72,11 @@ def load_library():
     vp, sz, ui, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint, ctypes.c_int
     lib.foldconv_plan.argtypes = [ci] * 10 + [ctypes.POINTER(vp)]
     lib.foldconv_plan.restype = ci
+    lib.foldconv_plan_nchw.argtypes = [ci] * 11 + [ctypes.POINTER(vp)]
+    lib.foldconv_plan_nchw.restype = ci
+    for name in ("foldconv_expand_filter_oihw", "foldconv_fold_input_nchw", "foldconv_unfold_output_nchw"):
+        getattr(lib, name).argtypes = [vp, vp, vp, vp]
+        getattr(lib, name).restype = ci
     lib.foldconv_plan_gemm.argtypes = [ctypes.c_longlong, ci, ci, ci, ci, ctypes.POINTER(vp)]
     lib.foldconv_plan_gemm.restype = ci
     lib.foldconv_choose_fold.argtypes = [ci] * 9 + [ctypes.POINTER(ci)]
@@ -143,6 +150,16 @@ def foldconv_plan(N, H, W, C_in, C_out, KH, KW, pad, fold_factor, dtype):
     return plan
 
 
+def foldconv_plan_nchw(N, C_in, H, W, C_out, KH, KW, pad, fold_factor, fold_axis, dtype):
+    lib = load_library()
+    h = ctypes.c_void_p()
+    _check(lib.foldconv_plan_nchw(N, C_in, H, W, C_out, KH, KW, pad, fold_factor, fold_axis, _dtype_code(dtype),
+                                  ctypes.byref(h)), "foldconv_plan_nchw")
+    plan = Plan(h, None)
+    plan.shapes = foldconv_plan_query(plan)
+    return plan
+
+
 def foldconv_plan_gemm(M, K, N, fold_factor, dtype):
     lib = load_library()
     h = ctypes.c_void_p()
@@ -204,6 +221,30 @@ def foldconv_expand_filter(plan, w, w_exp, stream=None):
     _need(w_exp, s.w_exp_bytes, "w_exp")
     _check(load_library().foldconv_expand_filter(plan.handle, _ptr(w), _ptr(w_exp), _stream(stream)),
            "foldconv_expand_filter")
+
+
+def foldconv_expand_filter_oihw(plan, w_oihw, w_exp, stream=None):
+    s = plan.shapes
+    _need(w_oihw, s.w_bytes, "w_oihw")
+    _need(w_exp, s.w_exp_bytes, "w_exp")
+    _check(load_library().foldconv_expand_filter_oihw(plan.handle, _ptr(w_oihw), _ptr(w_exp), _stream(stream)),
+           "foldconv_expand_filter_oihw")
+
+
+def foldconv_fold_input_nchw(plan, x_nchw, x_fold, stream=None):
+    s = plan.shapes
+    _need(x_nchw, s.x_bytes, "x_nchw")
+    _need(x_fold, s.x_bytes, "x_fold")
+    _check(load_library().foldconv_fold_input_nchw(plan.handle, _ptr(x_nchw), _ptr(x_fold), _stream(stream)),
+           "foldconv_fold_input_nchw")
+
+
+def foldconv_unfold_output_nchw(plan, y_fold, y_nchw, stream=None):
+    s = plan.shapes
+    _need(y_fold, s.y_fold_bytes, "y_fold")
+    _need(y_nchw, s.y_bytes, "y_nchw")
+    _check(load_library().foldconv_unfold_output_nchw(plan.handle, _ptr(y_fold), _ptr(y_nchw), _stream(stream)),
+           "foldconv_unfold_output_nchw")
 
 
 def foldconv_fold_input(plan, x, x_fold, stream=None):

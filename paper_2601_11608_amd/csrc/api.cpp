@@ -15,7 +15,33 @@ static const unsigned kAllFlags =
 
 extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
     if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
-    return hip_status(fc_launch_expand(plan, w, w_exp, stream));
+    return hip_status(fc_launch_expand(plan, w, w_exp, 0, stream));
+}
+
+extern "C" int foldconv_expand_filter_oihw(foldconv_plan_t plan, const void *w_oihw, void *w_exp, void *stream) {
+    if (!plan_ok(plan) || !w_oihw || !w_exp || w_oihw == w_exp) return FOLDCONV_ERR_BADARG;
+    return hip_status(fc_launch_expand(plan, w_oihw, w_exp, 1, stream));
+}
+
+static bool overlap(const void *a, long long na, const void *b, long long nb) {
+    const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+    return x < y + (uintptr_t)nb && y < x + (uintptr_t)na;
+}
+
+extern "C" int foldconv_fold_input_nchw(foldconv_plan_t plan, const void *x_nchw, void *x_fold, void *stream) {
+    if (!plan_ok(plan) || !x_nchw || !x_fold) return FOLDCONV_ERR_BADARG;
+    const size_t eb = (size_t)plan->s.elem_bytes;
+    if (!aligned(x_nchw, eb) || !aligned(x_fold, eb)) return FOLDCONV_ERR_BADARG;
+    if (overlap(x_nchw, plan->s.x_bytes, x_fold, plan->s.x_bytes)) return FOLDCONV_ERR_BADARG;
+    return hip_status(fc_launch_fold_nchw(plan, x_nchw, x_fold, stream));
+}
+
+extern "C" int foldconv_unfold_output_nchw(foldconv_plan_t plan, const void *y_fold, void *y_nchw, void *stream) {
+    if (!plan_ok(plan) || !y_fold || !y_nchw) return FOLDCONV_ERR_BADARG;
+    const size_t eb = (size_t)plan->s.elem_bytes;
+    if (!aligned(y_fold, eb) || !aligned(y_nchw, eb)) return FOLDCONV_ERR_BADARG;
+    if (overlap(y_fold, plan->s.y_fold_bytes, y_nchw, plan->s.y_bytes)) return FOLDCONV_ERR_BADARG;
+    return hip_status(fc_launch_unfold_nchw(plan, y_fold, y_nchw, stream));
 }
 
 extern "C" int foldconv_fold_input(foldconv_plan_t plan, const void *x, void *x_fold, void *stream) {

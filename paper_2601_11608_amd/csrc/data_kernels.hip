@@ -27,10 +27,17 @@ inline unsigned blocks_for(long long work, int per_block, long long cap) {
 //   w'[kh][dd][f*C+c][g*Co+co] = w[kh][F*(dd+d_min)+f-g+p][c][co]  if that tap
 //   index is inside [0, KW), else 0.
 // ---------------------------------------------------------------------------
+// The source filter is addressed through four element strides, so the same
+// kernel reads HWIO (strides KW*C*Co, C*Co, Co, 1) and OIHW with either image
+// axis in the role of the folded one.
+struct FilterStrides {
+    long long kh, kw, c, co;
+};
+
 template <typename U>
 __global__ void __launch_bounds__(kThreads)
 expand_filter_kernel(const U *__restrict__ w, U *__restrict__ we, int KH, int KW, int C, int Co, int F,
-                     int KWf, int d_min, int p, long long total) {
+                     int KWf, int d_min, int p, long long total, FilterStrides ws) {
     const long long stride = (long long)gridDim.x * kThreads;
     const int FC = F * C, FCo = F * Co;
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
@@ -44,7 +51,7 @@ expand_filter_kernel(const U *__restrict__ w, U *__restrict__ we, int KH, int KW
         int g = nn / Co, co = nn - g * Co;
         int kw = F * (dd + d_min) + f - g + p;
         U v = 0;
-        if (kw >= 0 && kw < KW) v = w[(((long long)kh * KW + kw) * C + c) * Co + co];
+        if (kw >= 0 && kw < KW) v = w[kh * ws.kh + kw * ws.kw + c * ws.c + co * ws.co];
         we[i] = v;
     }
 }
@@ -180,21 +187,169 @@ compact_filter_kernel(const uint16_t *__restrict__ w, u32x4 *__restrict__ cpk, i
     }
 }
 
+// ---------------------------------------------------------------------------
+// Channels-first front end (paper: Introduction, "height folding for NCHW
+// format").  A spatial axis of an NCHW tensor is not adjacent to the channel
+// axis in memory, so folding it into channels is a real re-index, not an alias.
+// The folded tensors keep the channels-last form the MFMA kernels read,
+//   x'[n][a][b'][f*C+c],  (a, F*b'+f) = (h, w) when W is folded, (w, h) when H is,
+// which as bytes is the plan-space NHWC tensor [n][a][b][c].
+//
+// Input: one thread builds one 16-byte piece of x' from scalar reads of x;
+// neighbouring lanes read neighbouring addresses of the same few channel planes, so the
+// reads coalesce in the vector L1.
+// ---------------------------------------------------------------------------
+struct NchwMap {
+    long long total;        // elements of the channels-last tensor
+    int C, A, B;            // channels, plan-space rows and columns
+    long long sC, sA, sB;   // element strides of (c, a, b) inside one NCHW image; image stride = C*A*B
+};
+
+template <typename U>
+__global__ void __launch_bounds__(kThreads)
+nchw_to_fold_kernel(const U *__restrict__ x, U *__restrict__ xf, NchwMap m, int vec) {
+    constexpr int EPC = 16 / sizeof(U);
+    const long long pieces = (m.total + EPC - 1) / EPC;
+    const long long stride = (long long)gridDim.x * kThreads;
+    const long long img = (long long)m.C * m.A * m.B;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < pieces; i += stride) {
+        long long e = i * EPC;
+        int c = (int)(e % m.C);
+        long long r = e / m.C;
+        int b = (int)(r % m.B);
+        r /= m.B;
+        int a = (int)(r % m.A);
+        long long n = r / m.A;
+        U v[EPC];
+#pragma unroll
+        for (int j = 0; j < EPC; ++j) {
+            v[j] = (e + j < m.total) ? x[n * img + c * m.sC + a * m.sA + b * m.sB] : (U)0;
+            if (++c == m.C) {
+                c = 0;
+                if (++b == m.B) {
+                    b = 0;
+                    if (++a == m.A) { a = 0; ++n; }
+                }
+            }
+        }
+        if (vec && e + EPC <= m.total) {
+            u32x4 out;
+            __builtin_memcpy(&out, v, 16);
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(xf) + i);
+        } else {
+#pragma unroll
+            for (int j = 0; j < EPC; ++j)
+                if (e + j < m.total) xf[e + j] = v[j];
+        }
+    }
+}
+
+// Output: y'[n][a][b][co] (row pitch in b given, columns b >= B cropped: the ragged
+// reconstruct) -> y[n][co][himg][wimg].  A workgroup moves a tile of 64 image columns x 64
+// channels of one image row through LDS: 16-byte loads along co, eight 2-byte LDS reads per
+// lane gather eight consecutive image columns of one channel, one 16-byte store along w.
+struct FoldToNchw {
+    int Co, Hi, Wi;             // channels, image rows and columns of y
+    long long sN, sH, sW;       // element strides of (n, himg, wimg) in y'
+    int tiles_w, tiles_c;
+    long long rows;             // N * Hi
+};
+
+constexpr int kTW = 64, kTC = 64;
+constexpr int kTPitch = kTC * 2 + 4;  // bytes per LDS row; 33 dwords: the column gather hits distinct banks
+
+__global__ void __launch_bounds__(kThreads)
+fold_to_nchw_tile_kernel(const uint16_t *__restrict__ yf, uint16_t *__restrict__ y, FoldToNchw m) {
+    __shared__ __attribute__((aligned(16))) unsigned char tile[kTW * kTPitch];
+    const long long per_row = (long long)m.tiles_w * m.tiles_c;
+    const long long total = m.rows * per_row;
+    const int t = threadIdx.x;
+    for (long long job = blockIdx.x; job < total; job += gridDim.x) {
+        const long long row = job / per_row;           // n * Hi + himg
+        const int rem = (int)(job - row * per_row);
+        const int w0 = (rem / m.tiles_c) * kTW, c0 = (rem % m.tiles_c) * kTC;
+        const long long n = row / m.Hi;
+        const int hi = (int)(row - n * m.Hi);
+        const uint16_t *src = yf + n * m.sN + hi * m.sH;
+        // load: 64 pixels x 8 chunks of 8 channels
+#pragma unroll
+        for (int i = 0; i < (kTW * kTC / 8) / kThreads; ++i) {
+            const int q = t + kThreads * i;
+            const int px = q >> 3, ch = q & 7;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (w0 + px < m.Wi && c0 + 8 * ch < m.Co)
+                v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + (w0 + px) * m.sW + c0 + 8 * ch));
+            unsigned *dst = reinterpret_cast<unsigned *>(tile + px * kTPitch + 16 * ch);
+            dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+        }
+        __syncthreads();
+        // store: per channel, 8 chunks of 8 consecutive image columns
+#pragma unroll
+        for (int i = 0; i < (kTW * kTC / 8) / kThreads; ++i) {
+            const int q = t + kThreads * i;
+            const int wc = q & 7, c = q >> 3;
+            const int wbase = w0 + 8 * wc;
+            if (c0 + c < m.Co && wbase < m.Wi) {
+                uint16_t v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    v[k] = *reinterpret_cast<const uint16_t *>(tile + (8 * wc + k) * kTPitch + 2 * c);
+                uint16_t *dst = y + ((n * m.Co + c0 + c) * m.Hi + hi) * (long long)m.Wi + wbase;
+                if (wbase + 8 <= m.Wi) {
+                    u32x4 out;
+                    __builtin_memcpy(&out, v, 16);
+                    __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(dst));
+                } else {
+                    for (int k = 0; k < 8 && wbase + k < m.Wi; ++k) dst[k] = v[k];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Any element size and alignment: one thread per element of y, writes coalesced along w.
+template <typename U>
+__global__ void __launch_bounds__(kThreads)
+fold_to_nchw_elem_kernel(const U *__restrict__ yf, U *__restrict__ y, FoldToNchw m) {
+    const long long total = m.rows * m.Co * m.Wi;
+    const long long stride = (long long)gridDim.x * kThreads;
+    for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        const int wi = (int)(i % m.Wi);
+        long long r = i / m.Wi;
+        const int hi = (int)(r % m.Hi);
+        r /= m.Hi;
+        const int co = (int)(r % m.Co);
+        const long long n = r / m.Co;
+        y[i] = yf[n * m.sN + hi * m.sH + wi * m.sW + co];
+    }
+}
+
 inline int last_error() { return (int)hipGetLastError(); }
 
 }  // namespace
 
-int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, void *stream) {
+int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, int oihw, void *stream) {
     const foldconv_shapes_t &s = p->s;
     const long long total = s.gemm_K * s.gemm_N;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
     hipStream_t st = (hipStream_t)stream;
+    FilterStrides ws;
+    if (!oihw) {
+        ws.co = 1; ws.c = s.C_out; ws.kw = (long long)s.C_in * s.C_out; ws.kh = ws.kw * s.KW;
+    } else {
+        // w[Co][C][KH_img][KW_img]; the plan's (KH, KW) are the image's (KH, KW), or (KW, KH) when H is folded
+        const long long taps = (long long)s.KH * s.KW;
+        ws.co = (long long)s.C_in * taps; ws.c = taps;
+        if (p->fold_axis == FOLDCONV_FOLD_H) { ws.kh = 1; ws.kw = s.KH; }
+        else { ws.kh = s.KW; ws.kw = 1; }
+    }
     if (s.elem_bytes == 2)
         expand_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (uint16_t *)w_exp, s.KH, s.KW,
-                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total);
+                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total, ws);
     else
         expand_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (uint32_t *)w_exp, s.KH, s.KW,
-                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total);
+                                                                   s.C_in, s.C_out, s.F, s.KW_fold, s.d_min, s.pad_w, total, ws);
     return last_error();
 }
 
@@ -282,5 +437,56 @@ int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
     compact_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH, g.KW * g.C, g.Co,
                                                      g.cJ, g.cgcd, total);
+    return last_error();
+}
+
+int fc_launch_fold_nchw(const foldconv_plan_s *p, const void *x, void *x_fold, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    NchwMap m;
+    m.C = s.C_in; m.A = s.H; m.B = s.W;
+    m.total = (long long)s.N * s.H * s.W * s.C_in;
+    m.sC = (long long)s.H * s.W;
+    if (p->fold_axis == FOLDCONV_FOLD_H) { m.sA = 1; m.sB = s.H; }   // image is [C][W_plan = H_img][H_plan = W_img]
+    else { m.sA = s.W; m.sB = 1; }
+    const int vec = ((uintptr_t)x_fold % 16 == 0) ? 1 : 0;
+    const long long pieces = (m.total * s.elem_bytes + 15) / 16;
+    const unsigned grid = blocks_for(pieces, kThreads, 1 << 22);
+    if (s.elem_bytes == 2)
+        nchw_to_fold_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)x, (uint16_t *)x_fold, m, vec);
+    else
+        nchw_to_fold_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)x, (uint32_t *)x_fold, m, vec);
+    return last_error();
+}
+
+int fc_launch_unfold_nchw(const foldconv_plan_s *p, const void *y_fold, void *y, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    FoldToNchw m;
+    const long long pitch_b = (long long)s.W_out_fold * s.Co_fold;  // elements per plan-space row of y'
+    m.Co = s.C_out;
+    m.sN = (long long)s.H_out * pitch_b;
+    if (p->fold_axis == FOLDCONV_FOLD_H) {
+        m.Hi = s.W_out; m.Wi = s.H_out;  // image rows run along the plan's folded axis
+        m.sH = s.C_out; m.sW = pitch_b;
+    } else {
+        m.Hi = s.H_out; m.Wi = s.W_out;
+        m.sH = pitch_b; m.sW = s.C_out;
+    }
+    m.rows = (long long)s.N * m.Hi;
+    m.tiles_w = (m.Wi + kTW - 1) / kTW;
+    m.tiles_c = (m.Co + kTC - 1) / kTC;
+    const bool tiled = s.elem_bytes == 2 && s.C_out % 8 == 0 && m.Wi % 8 == 0 &&
+                       ((uintptr_t)y_fold | (uintptr_t)y) % 16 == 0;
+    if (tiled) {
+        const unsigned grid = blocks_for(m.rows * m.tiles_w * m.tiles_c, 1, 1 << 22);
+        fold_to_nchw_tile_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)y_fold, (uint16_t *)y, m);
+    } else {
+        const unsigned grid = blocks_for(m.rows * m.Co * m.Wi, kThreads, 1 << 22);
+        if (s.elem_bytes == 2)
+            fold_to_nchw_elem_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)y_fold, (uint16_t *)y, m);
+        else
+            fold_to_nchw_elem_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)y_fold, (uint32_t *)y, m);
+    }
     return last_error();
 }

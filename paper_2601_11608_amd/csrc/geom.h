@@ -90,6 +90,7 @@ struct foldconv_plan_s {
     ConvGeom padc;  // the zero-padded problem, F = 1, C = C_pad
     // byte offsets inside the padded-path workspace
     size_t ws_xpad, ws_wpad, ws_wpack;
+    int fold_axis;  // FOLDCONV_FOLD_W, or FOLDCONV_FOLD_H for a channels-first plan built on the transposed image
 };
 
 #define FOLDCONV_MAGIC 0xF01DC0DEu

@@ -23,7 +23,9 @@ struct StreamShape {
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 
 // --- launchers (return 0 or a hipError_t value) -------------------------------
-int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, void *stream);
+int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, int oihw, void *stream);
+int fc_launch_fold_nchw(const foldconv_plan_s *p, const void *x, void *x_fold, void *stream);
+int fc_launch_unfold_nchw(const foldconv_plan_s *p, const void *y_fold, void *y, void *stream);
 int fc_launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int fc_launch_unfold(const foldconv_plan_s *p, const void *y_fold, void *y, void *stream);
 int fc_launch_pad_input(const foldconv_plan_s *p, const void *x, void *x_pad, void *stream);

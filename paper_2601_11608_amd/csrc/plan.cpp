@@ -139,6 +139,21 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     return FOLDCONV_OK;
 }
 
+extern "C" int foldconv_plan_nchw(int N, int C_in, int H, int W, int C_out, int KH, int KW, int pad,
+                                  int fold_factor, int fold_axis, foldconv_dtype_t dtype, foldconv_plan_t *out) {
+    if (!out) return FOLDCONV_ERR_BADARG;
+    *out = nullptr;
+    if (fold_axis != FOLDCONV_FOLD_W && fold_axis != FOLDCONV_FOLD_H) return FOLDCONV_ERR_BADARG;
+    // Height folding is width folding of the transposed image: rows and columns, KH and KW trade places.
+    const int st = fold_axis == FOLDCONV_FOLD_H
+                       ? foldconv_plan(N, W, H, C_in, C_out, KW, KH, pad, fold_factor, dtype, out)
+                       : foldconv_plan(N, H, W, C_in, C_out, KH, KW, pad, fold_factor, dtype, out);
+    if (st != FOLDCONV_OK) return st;
+    (*out)->fold_axis = fold_axis;
+    (*out)->s.fold_axis = fold_axis;
+    return FOLDCONV_OK;
+}
+
 extern "C" int foldconv_plan_gemm(long long M, int K, int N, int fold_factor, foldconv_dtype_t dtype,
                                   foldconv_plan_t *out) {
     if (!out) return FOLDCONV_ERR_BADARG;
