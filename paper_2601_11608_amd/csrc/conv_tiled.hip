@@ -2,10 +2,10 @@
 // filter-stationary streaming kernel (tens to hundreds of 16-wide K-steps):
 // there the matrix cores, not HBM, bound the layer.
 //
-// One 256-thread workgroup (4 waves, 2 x 2) computes a BN (output columns n)
-// x 128 (folded output pixels m) tile of y'^T, BN = 128 or 256; each wave a
-// (BN/2) x 64 quadrant as TN x 2 MFMA tiles of 32 x 32 (TN = 2 or 4: the wider
-// tile halves the LDS reads and the input re-reads per MFMA and is used when
+// One workgroup of 2 x WM waves computes a BN (output columns n) x BM (folded
+// output pixels m) tile of y'^T, BN = 128 or 256, BM = 64*WM (128 as built);
+// each wave a (BN/2) x 64 part as TN x 2 MFMA tiles of 32 x 32 (TN = 2 or 4: the
+// wider tile halves the LDS reads and the input re-reads per MFMA and is used when
 // there are enough output columns to fill it).  K = (kh, extended channel e) is walked in
 // blocks of 32 elements (two MFMA K-steps), restricted to the band of w' that
 // can be non-zero for the tile's output slots (paper: Eq. "filter_construct";
@@ -15,12 +15,17 @@
 //   filter: pack[kh][q][n][8] rows copied as they are (coalesced),
 //   input:  the window chunk [e, e+8) of each pixel's input row, a 16-byte
 //           range-checked buffer load (zero padding = out-of-range offset).
-// Global loads for block i+1 are issued before the MFMAs of block i and
-// written to the other LDS stage afterwards: one barrier per K block.
+// The K loop is one software pipeline: while block b is multiplied, the global
+// loads of block b+2 and the LDS writes of block b+1 are issued one per MFMA
+// step, and the LDS fragment reads run two steps ahead of the MFMAs that use
+// them; one barrier per K block.  The staging loads are inline assembly with
+// explicit wait counts (checked by a test that walks the generated code).
 // Epilogue: bias as a rank-1 MFMA, ReLU, one rounding, transpose through LDS,
 // 16-byte row-contiguous stores with the reconstruct step fused in.
 // paper: Eq. "new_conv_H", Eq. "bias_construct", Reconstruct step.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "launch.h"
 #include "mfma_types.h"
@@ -30,12 +35,12 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 128, BK = 32;
+constexpr int BK = 32;
 constexpr int QPB = BK / 8;                 // 16-byte chunks per row per K block
 constexpr unsigned kOutOfRange = 0x80000000u;
 
-// LDS geometry for a tile of BN output columns
-template <int BN>
+// LDS geometry for a tile of BN output columns x BM pixels
+template <int BN, int BM>
 struct TileLds {
     // bytes of one chunk plane; the pad staggers the planes so that the 16 lanes of a staging write
     // (QPB chunks x 16/QPB pixels) fall on 16 distinct bank groups
@@ -43,7 +48,7 @@ struct TileLds {
     static constexpr int PLANE_I = BM * 16 + 256 / QPB;
     static constexpr int STAGE = QPB * (PLANE_F + PLANE_I);  // filter planes then input planes
     static constexpr int EPITCH = BN * 2 + 16;               // bytes per row of the transposed output half-tile
-    static constexpr int EBYTES = 64 * EPITCH;               // the epilogue handles 64 pixels at a time
+    static constexpr int EBYTES = (BM / 2) * EPITCH;         // the epilogue handles one 32-pixel MFMA row per wave at a time
     static constexpr int BYTES = (2 * STAGE > EBYTES) ? 2 * STAGE : EBYTES;
 };
 
@@ -69,14 +74,16 @@ struct TiledArgs {
     unsigned x_bytes, wp_bytes;
 };
 
-template <typename TR, int TN, bool RELU>
-__global__ void __launch_bounds__(256, 2)
+template <typename TR, int TN, int WM, bool RELU>
+__global__ void __launch_bounds__(128 * WM, WM == 2 ? 2 : 1)
 conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                   const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
     using T = typename TR::T;
     using Vec = typename TR::Vec;
-    constexpr int BN = 64 * TN;
-    using L = TileLds<BN>;
+    constexpr int BN = 64 * TN;        // two wave columns of TN MFMA tiles
+    constexpr int BM = 64 * WM;        // WM wave rows of two MFMA tiles
+    constexpr int THREADS = 128 * WM;  // 2 x WM waves
+    using L = TileLds<BN, BM>;
     constexpr int PLANE_F = L::PLANE_F, PLANE_I = L::PLANE_I, STAGE = L::STAGE, EPITCH = L::EPITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds[L::BYTES];
 
@@ -99,104 +106,140 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     const int T_total = g.KH * kblocks;
     const int q_per_kh = g.kwin / 8;
 
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(x), 0, (int)a.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4 *>(wp), 0, (int)a.wp_bytes, 0x00020000);
+    // Range-checked raw buffer resources (byte offsets; an offset beyond the extent reads as zero).
+    // They are built by hand as SGPR quads because the staging loads below are inline assembly.
+    auto make_srd = [](const void *p, unsigned bytes) {
+        const unsigned long long a = (unsigned long long)p;
+        u32x4 r;
+        r[0] = __builtin_amdgcn_readfirstlane((unsigned)a);
+        r[1] = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32) & 0xffffu);
+        r[2] = __builtin_amdgcn_readfirstlane(bytes);
+        r[3] = __builtin_amdgcn_readfirstlane(0x00020000u);
+        return r;
+    };
+    u32x4 xr = make_srd(x, a.x_bytes);  // not const: the generic lambdas below must capture them for asm operands
+    u32x4 wr = make_srd(wp, a.wp_bytes);
 
     // ---- this thread's share of the staging loads -----------------------------
     // input: chunk column qi of NI pixels, one 16-byte chunk each
-    constexpr int NI = (BM * QPB) / 256;   // input chunks per thread per K block
-    constexpr int NF = (BN * QPB) / 256;   // filter chunks per thread per K block
-    constexpr int MSTEP = 256 / QPB;       // pixels covered by one pass of the 256 threads
+    constexpr int NI = (BM * QPB) / THREADS;   // input chunks per thread per K block
+    constexpr int NF = (BN * QPB) / THREADS;   // filter chunks per thread per K block
+    constexpr int NL = NI + NF;                // staging loads per thread per K block
+    constexpr int MSTEP = THREADS / QPB;       // pixels covered by one pass of the workgroup
     const int qi = t & (QPB - 1);
     int pix[NI], ho_[NI], col_[NI];
-    bool vm[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
         const unsigned m = m0 + (unsigned)(t / QPB) + (unsigned)(MSTEP * i);
-        vm[i] = m < (unsigned)g.M;
-        const unsigned mm = vm[i] ? m : 0u;
+        const bool vm = m < (unsigned)g.M;
+        const unsigned mm = vm ? m : 0u;
         const unsigned wo = mm % (unsigned)g.Wf_out;
         const unsigned rowid = mm / (unsigned)g.Wf_out;
         const unsigned ho = rowid % (unsigned)g.Hout;
         const unsigned img = rowid / (unsigned)g.Hout;
-        ho_[i] = (int)ho;
+        ho_[i] = vm ? (int)ho : -0x40000000;  // a pixel past the end fails every row test below
         col_[i] = (int)wo * g.FC + 8 * qi;
         pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
     }
-    // filter: BN columns x QPB planes = NF chunks per thread, column-contiguous across threads
     // The chunk for window chunk q of a column sits at  fbase + (kh*f_jmax + (q - fj0)) * f_stride
     // when 0 <= q - fj0 < f_jmax.  Packed w': one run of q_per_kh chunks per kh, column stride NCo.
     // Compact storage: the column's slot fixes the phase copy and the first window chunk its tap
     // matrix reaches (fc_compact_chunk); chunks outside are structural zeros.
     int nf[NF], qf[NF], fbase[NF], fj0[NF];
-    bool vn[NF];
     const int f_jmax = g.compact ? g.cJ : q_per_kh;
     const int f_stride = g.compact ? g.Co : g.NCo;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        const int idx = t + 256 * i;
+        const int idx = t + THREADS * i;
         nf[i] = idx % BN;
         qf[i] = idx / BN;
-        vn[i] = n0 + nf[i] < g.NCo;
-        const int n = vn[i] ? n0 + nf[i] : 0;
+        const bool vn = n0 + nf[i] < g.NCo;
+        const int n = vn ? n0 + nf[i] : 0;
         if (g.compact) {
             const int slot = n / g.Co, co = n - slot * g.Co;
-            const int a = (slot - g.pad_w) * g.C - g.e_min;
-            fj0[i] = a >> 3;
-            fbase[i] = ((a & 7) / g.cgcd) * g.KH * g.cJ * g.Co + co;
+            const int a_g = (slot - g.pad_w) * g.C - g.e_min;
+            fj0[i] = a_g >> 3;
+            fbase[i] = ((a_g & 7) / g.cgcd) * g.KH * g.cJ * g.Co + co;
         } else {
             fj0[i] = 0;
             fbase[i] = n;
         }
+        if (!vn) fj0[i] = 0x40000000;  // a column past the end fails the chunk range test below
     }
 
-    // Two register sets: the loads of block i+2 are issued while block i is computed and are
-    // written to LDS one step later, so they have a whole step of MFMAs (of this and of the
-    // co-resident workgroup) to land.
+    // Staging loads are issued from inline assembly and waited for with explicit counts: left to
+    // itself the compiler wraps every address select in a branch and waits for the loads of the
+    // previous K block at the top of the loop.  Vector-memory loads return in issue order, so
+    // "at most NL outstanding" means every load older than the NL newest has landed.
+    // Nothing else in the K loop touches vector memory.  The pipeline below has one code path:
+    // blocks past the end are issued with every lane out of range (no memory traffic, zeros
+    // returned) and committed to a stage nobody reads; what is still in flight when the loop
+    // ends is drained before any register is reused.
     struct StageRegs {
-        u32x4 ri[NI], rf[NF];
+        u32x4 r[NL];
     };
     StageRegs ra, rb;
-    int kh_l = 0, kb_l = 0;  // next block to load
-    auto load_block = [&](StageRegs &rg) {
+    int kh_l = 0, kb_l = 0;  // next block to issue
+    int is_kh = 0, is_e0 = 0;  // block being issued (wave-uniform)
+    auto issue_begin = [&]() {
         const bool live = kh_l < g.KH;
-        const int kh = live ? kh_l : 0;
-        const int e0 = live ? e_lo + kb_l * BK : e_hi;  // past the window: every lane out of range
-        u32x4 (&ri)[NI] = rg.ri;
-        u32x4 (&rf)[NF] = rg.rf;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int hi = ho_[i] + kh - g.pad_h;
-            const int e = e0 + 8 * qi;
-            const int col = col_[i] + e0;
-            const bool ok = vm[i] && hi >= 0 && hi < g.H && e < e_hi && col >= 0 && col < g.in_row;
-            const unsigned off = ok ? 2u * (unsigned)(pix[i] + kh * g.in_row + e0) : kOutOfRange;
-            ri[i] = __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < NF; ++i) {
-            const int e = e0 + 8 * qf[i];
-            const int j = ((e - g.e_min) >> 3) - fj0[i];
-            const bool ok = vn[i] && e < e_hi && j >= 0 && j < f_jmax;
-            const unsigned off = ok ? 16u * ((unsigned)fbase[i] + (unsigned)(kh * f_jmax + j) * (unsigned)f_stride) : kOutOfRange;
-            rf[i] = __builtin_amdgcn_raw_buffer_load_b128(wr, off, 0, 0);
-        }
+        is_kh = live ? kh_l : 0;
+        is_e0 = live ? e_lo + kb_l * BK : e_hi;  // past the window: every lane out of range
         if (++kb_l == kblocks) {
             kb_l = 0;
             ++kh_l;
         }
     };
-    auto store_block = [&](const StageRegs &rg, int stage) {
-        const u32x4 (&ri)[NI] = rg.ri;
-        const u32x4 (&rf)[NF] = rg.rf;
+    // load number `idx` of the block (a constant once the caller's loop is unrolled): NI input
+    // chunks, then NF filter chunks
+    auto issue_one = [&](StageRegs &rg, int idx) {
+        const int kh = is_kh, e0 = is_e0;
+        if (idx < NI) {
+            const int i = idx < NI ? idx : 0;
+            const int hi = ho_[i] + kh - g.pad_h;
+            const int col = col_[i] + e0;
+            const int ok = (int)((unsigned)hi < (unsigned)g.H) & (int)((unsigned)col < (unsigned)g.in_row) &
+                           (int)(e0 + 8 * qi < e_hi);
+            const unsigned val = 2u * (unsigned)(pix[i] + kh * g.in_row + e0);
+            const unsigned off = ok ? val : kOutOfRange;
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(rg.r[i]) : "v"(off), "s"(xr) : "memory");
+        } else {
+            const int i = idx < NI ? 0 : idx - NI;
+            const int e = e0 + 8 * qf[i];
+            const int j = ((e - g.e_min) >> 3) - fj0[i];
+            const int ok = (int)(e < e_hi) & (int)((unsigned)j < (unsigned)f_jmax);
+            const unsigned val = 16u * ((unsigned)fbase[i] + (unsigned)(kh * f_jmax + j) * (unsigned)f_stride);
+            const unsigned off = ok ? val : kOutOfRange;
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(rg.r[NI + i]) : "v"(off), "s"(wr) : "memory");
+        }
+    };
+    auto issue = [&](StageRegs &rg) {
+        issue_begin();
+#pragma unroll
+        for (int k = 0; k < NL; ++k) issue_one(rg, k);
+    };
+    // One wait that names every register of the set, so the set stays allocated until it has landed:
+    // returns once at most `count` younger loads are outstanding.
+    auto wait_set = [&](StageRegs &rg, auto count) {
+        constexpr int N = decltype(count)::value;
+        if constexpr (NL == 4)
+            asm volatile("s_waitcnt vmcnt(%4)" : "+v"(rg.r[0]), "+v"(rg.r[1]), "+v"(rg.r[2]), "+v"(rg.r[3]) : "n"(N) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%6)"
+                         : "+v"(rg.r[0]), "+v"(rg.r[1]), "+v"(rg.r[2]), "+v"(rg.r[3]), "+v"(rg.r[4]), "+v"(rg.r[5])
+                         : "n"(N) : "memory");
+    };
+    static_assert(NL == 4 || NL == 6, "wait_set lists the staging registers explicitly");
+    auto commit_one = [&](StageRegs &rg, int stage, int idx) {
         unsigned char *sf = lds + stage * STAGE;
         unsigned char *si = sf + QPB * PLANE_F;
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-            *reinterpret_cast<u32x4 *>(si + qi * PLANE_I + (t / QPB + MSTEP * i) * 16) = ri[i];
-#pragma unroll
-        for (int i = 0; i < NF; ++i)
-            *reinterpret_cast<u32x4 *>(sf + qf[i] * PLANE_F + nf[i] * 16) = rf[i];
+        if (idx < NI) {
+            const int i = idx < NI ? idx : 0;
+            *reinterpret_cast<u32x4 *>(si + qi * PLANE_I + (t / QPB + MSTEP * i) * 16) = rg.r[i];
+        } else {
+            const int i = idx < NI ? 0 : idx - NI;
+            *reinterpret_cast<u32x4 *>(sf + qf[i] * PLANE_F + nf[i] * 16) = rg.r[NI + i];
+        }
     };
 
     // ---- accumulators, initialised with the bias through a rank-1 MFMA ----------
@@ -222,41 +265,75 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     }
 
     // ---- K loop -----------------------------------------------------------------
-    auto compute = [&](int stage) {
+    // One K block = BK/16 MFMA K-steps x TN filter fragments, walked as a rolling pipeline: the
+    // fragment for step k+2 is requested from LDS before the two MFMAs of step k are issued, so
+    // an LDS round trip has 128 cycles of matrix work to hide behind.  The staging traffic of the
+    // blocks ahead is woven into the same instruction stream instead of following it: the global
+    // loads of block b+2 go out after the first step, and the LDS writes of block b+1 (into the
+    // stage nobody reads during this block) after the middle one, so they complete under the
+    // remaining MFMAs and the wave reaches the barrier with nothing left to wait for.  The
+    // scheduling fences keep the compiler from regrouping any of it.
+    auto block = [&](int stage, StageRegs &next2, StageRegs &next1) {
         const unsigned char *sf = lds + stage * STAGE;
         const unsigned char *si = sf + QPB * PLANE_F;
+        constexpr int KS = BK / 16, STEPS = KS * TN;
+        constexpr int W = STEPS - NL;  // first step that writes to LDS (earlier placements measured the same)
+        static_assert(W >= 0 && W + NL <= STEPS && NL <= STEPS, "one staging load and one staging write per step");
+        Vec fr[3], in[KS][2];
+        auto read_f = [&](int k) {
+            const int qc = 2 * (k / TN) + hf;
+            return *reinterpret_cast<const Vec *>(sf + qc * PLANE_F + (wn * (BN / 2) + (k % TN) * 32 + r) * 16);
+        };
+        auto read_i = [&](int ks, int mt) {
+            const int qc = 2 * ks + hf;
+            return *reinterpret_cast<const Vec *>(si + qc * PLANE_I + (wm * 64 + mt * 32 + r) * 16);
+        };
+        issue_begin();
+        in[0][0] = read_i(0, 0);
+        in[0][1] = read_i(0, 1);
+        fr[0] = read_f(0);
+        fr[1] = read_f(1);
 #pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            const int qc = 2 * s + hf;
-            Vec af[TN], bfv[2];
+        for (int k = 0; k < STEPS; ++k) {
+            if (k + 2 < STEPS) fr[(k + 2) % 3] = read_f(k + 2);
 #pragma unroll
-            for (int nt = 0; nt < TN; ++nt)
-                af[nt] = *reinterpret_cast<const Vec *>(sf + qc * PLANE_F + (wn * (BN / 2) + nt * 32 + r) * 16);
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-                bfv[mt] = *reinterpret_cast<const Vec *>(si + qc * PLANE_I + (wm * 64 + mt * 32 + r) * 16);
-#pragma unroll
-            for (int nt = 0; nt < TN; ++nt)
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) acc[nt][mt] = TR::mfma(af[nt], bfv[mt], acc[nt][mt]);
+            for (int ks = 1; ks < KS; ++ks)
+                if (k == ks * TN - 2) {
+                    in[ks][0] = read_i(ks, 0);
+                    in[ks][1] = read_i(ks, 1);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            const int ks = k / TN, nt = k % TN;
+            acc[nt][0] = TR::mfma(fr[k % 3], in[ks][0], acc[nt][0]);
+            acc[nt][1] = TR::mfma(fr[k % 3], in[ks][1], acc[nt][1]);
+            __builtin_amdgcn_sched_barrier(0);
+            // staging work of this step: one global load of block b+2, and from step W on one LDS
+            // write of block b+1 (its loads are older than the k+1 loads of b+2 issued so far)
+            if (k < NL) issue_one(next2, k);
+            if (k == W) wait_set(next1, std::integral_constant<int, (W + 1 < NL ? W + 1 : NL)>{});
+            if (k >= W && k < W + NL) commit_one(next1, stage ^ 1, k - W);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // Blocks past the end load nothing (out-of-range offsets) and are never computed.
-    load_block(ra);
-    load_block(rb);
-    store_block(ra, 0);
+    // Software pipeline over K blocks b = 0 .. T_total-1 (set and stage of block b: b & 1): while
+    // block b is multiplied, block b+2 is requested from memory and block b+1 is written to LDS.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing the compiler tracks may be in flight
+    issue(ra);
+    issue(rb);
+    wait_set(ra, std::integral_constant<int, NL>{});
+#pragma unroll
+    for (int k = 0; k < NL; ++k) commit_one(ra, 0, k);
     __syncthreads();
     for (int it = 0; it < T_total; it += 2) {
-        load_block(ra);        // block it+2
-        compute(0);            // block it
-        store_block(rb, 1);    // block it+1
+        block(0, ra, rb);  // multiply block it, request it+2 into ra, write it+1 from rb to stage 1
         __syncthreads();
         if (it + 1 >= T_total) break;
-        load_block(rb);        // block it+3
-        compute(1);            // block it+1
-        store_block(ra, 0);    // block it+2
+        block(1, rb, ra);  // multiply block it+1, request it+3 into rb, write it+2 from ra to stage 0
         __syncthreads();
     }
+    // the set issued last was never committed: let it land before its registers are reused
+    wait_set(ra, std::integral_constant<int, 0>{});
+    wait_set(rb, std::integral_constant<int, 0>{});
 
     // ---- epilogue: round, ReLU, transpose through LDS (stages are free after the last barrier),
     // 64 pixels (one MFMA tile row per wave) at a time ----
@@ -281,8 +358,8 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         __syncthreads();
         constexpr int CPR = BN / 8;  // 16-byte chunks per row
 #pragma unroll
-        for (int i = 0; i < (64 * CPR) / 256; ++i) {
-            const int idx = i * 256 + t;
+        for (int i = 0; i < (32 * WM * CPR) / THREADS; ++i) {
+            const int idx = i * THREADS + t;
             const int row = idx / CPR, ch = idx % CPR;
             const unsigned m = m0 + (unsigned)((row >> 5) * 64 + mt * 32 + (row & 31));
             const int n = n0 + 8 * ch;
@@ -300,10 +377,10 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     }
 }
 
-template <typename TR, int TN>
+template <typename TR, int TN, int WM>
 int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
-    constexpr int BN = 64 * TN;
+    constexpr int BN = 64 * TN, BM = 64 * WM, THREADS = 128 * WM;
     TiledArgs a;
     a.tiles_n = (unsigned)((g.NCo + BN - 1) / BN);
     a.tiles_m = (unsigned)((g.M + BM - 1) / BM);
@@ -316,15 +393,17 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
                            : (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
     const unsigned blocks = a.per_xcd * 8;
     if (g.relu)
-        conv_tiled_kernel<TR, TN, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+        conv_tiled_kernel<TR, TN, WM, true><<<blocks, THREADS, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     else
-        conv_tiled_kernel<TR, TN, false><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+        conv_tiled_kernel<TR, TN, WM, false><<<blocks, THREADS, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     return (int)hipGetLastError();
 }
 
 template <typename TR>
 int launch_any(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    return fc_tiled_bn(g) == 256 ? launch<TR, 4>(g, x, wp, bias, y, st) : launch<TR, 2>(g, x, wp, bias, y, st);
+    // A 256 x 256 tile on eight waves (WM = 4) moves a third fewer operand bytes per multiply but
+    // measured the same as 256 x 128 on the layers it fits, so only WM = 2 is instantiated.
+    return fc_tiled_bn(g) == 256 ? launch<TR, 4, 2>(g, x, wp, bias, y, st) : launch<TR, 2, 2>(g, x, wp, bias, y, st);
 }
 
 }  // namespace
