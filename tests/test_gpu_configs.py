@@ -56,3 +56,42 @@ def test_config_matches_oracle(env, oracle, name, images, mode):
     err = rel_l2_per_image(got, ref)
     print("config %s %s: rel-L2 = %.3e (tol %.1e)" % (name, mode, err, TOL[layers[0].dtype]), flush=True)
     assert err <= TOL[layers[0].dtype]
+
+
+def test_output_beyond_four_gigabytes(env, oracle):
+    """Largest-size case: a tall-skinny product whose output (8.6 GB) needs more than 32 bits of
+    byte offset, in the launch configuration the benchmark uses (packed filter, aliased fold).
+    Rows are independent, so the oracle checks sampled row blocks from the start, the quarters,
+    across the 4 GiB byte mark, and the end; every 16 Mi-th row block is also checked for
+    unwritten elements."""
+    fc, runner, wl = env
+    M, K, N, F = 1 << 26, 8, 64, 4
+    plan = fc.foldconv_plan_gemm(M, K, N, F, torch.float16)
+    s = plan.shapes
+    assert s.y_bytes == M * N * 2 >= (1 << 33) and s.conv_kernel == 2
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4242)
+    A = torch.randn((M, K), generator=g, dtype=torch.float32).to(torch.float16)
+    B = (torch.randn((K, N), generator=g, dtype=torch.float32) / np.sqrt(K)).to(torch.float16)
+    print("large gemm: inputs drawn", flush=True)
+    xd, wd = A.cuda(), B.cuda()
+    w_exp = torch.empty(s.w_exp_bytes // 2, dtype=torch.float16, device="cuda")
+    fc.foldconv_expand_filter(plan, wd, w_exp)
+    ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+    fc.foldconv_pack_filter(plan, w_exp, ws)
+    y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    fc.foldconv_fold_input(plan, xd, xd)
+    fc.foldconv_forward(plan, xd, w_exp, None, y, ws, fc.FLAG_FILTER_PACKED)
+    torch.cuda.synchronize()
+    print("large gemm: kernel done", flush=True)
+    rows_per_4g = (1 << 32) // (N * 2)
+    assert rows_per_4g == M // 2
+    starts = [0, M // 4 + 32, rows_per_4g - 64, 3 * (M // 4) - 32, M - 128]
+    Bf = f64(B)
+    for r0 in starts:
+        got = f64(y[r0:r0 + 128].cpu())
+        ref = oracle.conv_direct(f64(A[r0:r0 + 128]).reshape(1, 1, 128, K), Bf.reshape(1, 1, K, N), None, 0, 0)
+        assert rel_l2_per_image(got.reshape(1, -1), ref.reshape(1, -1)) <= TOL["f16"], r0
+    for r0 in range(0, M, 1 << 24):
+        assert not bool(torch.isnan(y[r0:r0 + 4096]).any()), r0
+    assert not bool(torch.isnan(y[-4096:]).any())
