@@ -85,7 +85,9 @@ typedef struct foldconv_shapes_s {
     int32_t pad_left_fold, pad_right_fold; /* zero columns the folded problem needs          */
     int32_t H_out, W_out, W_out_fold;      /* W_out_fold = ceil(W_out / F)                    */
     int32_t unfold_is_alias;        /* 1 when y and y' are the same bytes (W_out == F*W'_out) */
-    int32_t C_pad;                  /* channel count used by conv_padded_forward              */
+    int32_t C_pad;                  /* input channel count used by conv_padded_forward        */
+    int32_t C_out_pad;              /* its output channel count (C_out rounded up to 8 for
+                                       16-bit types; the result is cropped back to C_out)     */
     int32_t elem_bytes;
     int32_t conv_kernel;            /* 0 = gather MFMA, 1 = LDS-tiled MFMA, 2 = streaming MFMA
                                        (which kernel foldconv_forward will launch)            */
@@ -257,7 +259,9 @@ FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, cons
 
 /*
  * Reference path: zero-pad C_in up to shapes.C_pad in the input and the
- * filter, then run the same convolution kernels unfolded (F = 1).
+ * filter (and C_out up to shapes.C_out_pad in the filter and the bias), run
+ * the same convolution kernels unfolded (F = 1), and crop the result back to
+ * C_out channels when C_out was padded.
  * paper: the zero-padding alternative in the Introduction and in "Difference
  * from Channel Zero-Padding".  x and w are the ORIGINAL tensors; the padded
  * copies live in workspace (shapes.padded_workspace_bytes).  With

@@ -141,8 +141,10 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
     if (st) return st;
     char *ws = (char *)workspace;
     void *x_pad = ws + plan->ws_xpad, *w_pad = ws + plan->ws_wpad, *w_pack = ws + plan->ws_wpack;
+    const bool pad_out = s.C_out_pad != s.C_out;  // the kernels write C_out_pad channels per pixel, cropped below
+    void *b_pad = ws + plan->ws_bpad, *y_pad = ws + plan->ws_ypad;
     const int kernel = s.padded_kernel;
-    if (kernel != FC_KERNEL_GATHER && !aligned(y, 16)) return FOLDCONV_ERR_BADARG;
+    if (kernel != FC_KERNEL_GATHER && !pad_out && !aligned(y, 16)) return FOLDCONV_ERR_BADARG;
 
     int e = fc_launch_pad_input(plan, x, x_pad, stream);
     if (e) return FOLDCONV_ERR_HIP;
@@ -154,9 +156,17 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
             if (e) return FOLDCONV_ERR_HIP;
         }
     }
+    if (pad_out && bias) {  // the bias is an argument of every call: pad it every time
+        e = fc_launch_pad_bias(plan, bias, b_pad, stream);
+        if (e) return FOLDCONV_ERR_HIP;
+    }
     ConvGeom g = plan->padc;
     g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
     g.band = 1;
     g.has_bias = bias ? 1 : 0;
-    return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_pad, w_pad, w_pack, bias, y, stream));
+    e = fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_pad, w_pad, w_pack, pad_out && bias ? b_pad : bias,
+                       pad_out ? y_pad : y, stream);
+    if (e) return FOLDCONV_ERR_HIP;
+    if (pad_out) return hip_status(fc_launch_crop_channels(plan, y_pad, y, stream));
+    return FOLDCONV_OK;
 }

@@ -122,15 +122,15 @@ pad_input_kernel(const U *__restrict__ x, U *__restrict__ xp, long long pixels, 
 
 template <typename U>
 __global__ void __launch_bounds__(kThreads)
-pad_filter_kernel(const U *__restrict__ w, U *__restrict__ wp, int taps, int C, int C_pad, int Co) {
-    const long long total = (long long)taps * C_pad * Co;
+pad_filter_kernel(const U *__restrict__ w, U *__restrict__ wp, int taps, int C, int C_pad, int Co, int Co_pad) {
+    const long long total = (long long)taps * C_pad * Co_pad;
     const long long stride = (long long)gridDim.x * kThreads;
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
-        int co = (int)(i % Co);
-        long long r = i / Co;
+        int co = (int)(i % Co_pad);
+        long long r = i / Co_pad;
         int c = (int)(r % C_pad);
         long long t = r / C_pad;
-        wp[i] = c < C ? w[(t * C + c) * Co + co] : (U)0;
+        wp[i] = (c < C && co < Co) ? w[(t * C + c) * Co + co] : (U)0;
     }
 }
 
@@ -412,12 +412,36 @@ int fc_launch_pad_filter(const foldconv_plan_s *p, const void *w, void *w_pad, v
     const foldconv_shapes_t &s = p->s;
     hipStream_t st = (hipStream_t)stream;
     const int taps = s.KH * s.KW;
-    const long long total = (long long)taps * s.C_pad * s.C_out;
+    const long long total = (long long)taps * s.C_pad * s.C_out_pad;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
     if (s.elem_bytes == 2)
-        pad_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (uint16_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out);
+        pad_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (uint16_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out, s.C_out_pad);
     else
-        pad_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (uint32_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out);
+        pad_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (uint32_t *)w_pad, taps, s.C_in, s.C_pad, s.C_out, s.C_out_pad);
+    return last_error();
+}
+
+// bias [C_out] -> [C_out_pad], zeros appended (the filter padding with one tap and one input channel)
+int fc_launch_pad_bias(const foldconv_plan_s *p, const void *b, void *b_pad, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    if (s.elem_bytes == 2)
+        pad_filter_kernel<uint16_t><<<1, kThreads, 0, st>>>((const uint16_t *)b, (uint16_t *)b_pad, 1, 1, 1, s.C_out, s.C_out_pad);
+    else
+        pad_filter_kernel<uint32_t><<<1, kThreads, 0, st>>>((const uint32_t *)b, (uint32_t *)b_pad, 1, 1, 1, s.C_out, s.C_out_pad);
+    return last_error();
+}
+
+// y_pad [pixels][C_out_pad] -> y [pixels][C_out]
+int fc_launch_crop_channels(const foldconv_plan_s *p, const void *y_pad, void *y, void *stream) {
+    const foldconv_shapes_t &s = p->s;
+    hipStream_t st = (hipStream_t)stream;
+    const long long pixels = (long long)s.N * s.H_out * s.W_out;
+    const unsigned grid = blocks_for(pixels * s.C_out, kThreads, 1 << 22);
+    if (s.elem_bytes == 2)
+        crop_rows_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)y_pad, (uint16_t *)y, pixels, s.C_out_pad, s.C_out);
+    else
+        crop_rows_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)y_pad, (uint32_t *)y, pixels, s.C_out_pad, s.C_out);
     return last_error();
 }
 

@@ -89,7 +89,7 @@ struct foldconv_plan_s {
     ConvGeom fold;  // the folded problem (band/relu/out_row/has_bias filled per call)
     ConvGeom padc;  // the zero-padded problem, F = 1, C = C_pad
     // byte offsets inside the padded-path workspace
-    size_t ws_xpad, ws_wpad, ws_wpack;
+    size_t ws_xpad, ws_wpad, ws_wpack, ws_bpad, ws_ypad;
     int fold_axis;  // FOLDCONV_FOLD_W, or FOLDCONV_FOLD_H for a channels-first plan built on the transposed image
 };
 

@@ -30,6 +30,8 @@ int fc_launch_copy(const void *src, void *dst, size_t bytes, void *stream);
 int fc_launch_unfold(const foldconv_plan_s *p, const void *y_fold, void *y, void *stream);
 int fc_launch_pad_input(const foldconv_plan_s *p, const void *x, void *x_pad, void *stream);
 int fc_launch_pad_filter(const foldconv_plan_s *p, const void *w, void *w_pad, void *stream);
+int fc_launch_pad_bias(const foldconv_plan_s *p, const void *b, void *b_pad, void *stream);
+int fc_launch_crop_channels(const foldconv_plan_s *p, const void *y_pad, void *y, void *stream);
 int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream);
 int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_compact, void *stream);
 int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp,

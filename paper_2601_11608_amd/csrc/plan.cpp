@@ -63,6 +63,10 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     const long long M = (long long)N * H_out * Wf_out;
     const long long K = (long long)KH * KWf * FC;
     const int C_pad = (C_in + 7) / 8 * 8;  // the alignment the paper names for fp16 tensor cores
+    // The reference path pads the output channels of 16-bit layers the same way, so that it runs the
+    // vector kernels too (an unfolded output with C_out off the 16-byte chunk alignment would
+    // otherwise fall to the element-gather kernel); the padded result is cropped by a copy.
+    const int Co_pad = eb == 2 ? (C_out + 7) / 8 * 8 : C_out;
 
     // Limits of the kernels' 32-bit tile arithmetic.
     const long long lim = (long long)INT_MAX / 4;
@@ -84,7 +88,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     s.pad_right_fold = (int)(Wf_out - Wf + d_min + KWf - 1);
     s.H_out = (int)H_out; s.W_out = (int)W_out; s.W_out_fold = (int)Wf_out;
     s.unfold_is_alias = (W_out == Wf_out * F) ? 1 : 0;
-    s.C_pad = C_pad; s.elem_bytes = eb;
+    s.C_pad = C_pad; s.C_out_pad = Co_pad; s.elem_bytes = eb;
     s.gemm_M = M; s.gemm_N = FCo; s.gemm_K = K;
     s.x_bytes = (long long)N * H * W * C_in * eb;
     s.w_bytes = (long long)KH * KW * C_in * C_out * eb;
@@ -106,17 +110,18 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     // Zero-padded reference problem: F = 1, every pixel C_pad channels.
     ConvGeom &q = p->padc;
     q.N = N; q.H = H; q.Hout = (int)H_out; q.Wf = W; q.Wf_out = (int)W_out;
-    q.FC = C_pad; q.NCo = C_out; q.Co = C_out; q.C = C_pad; q.F = 1; q.KH = KH; q.KW = KW;
+    q.FC = C_pad; q.NCo = Co_pad; q.Co = Co_pad; q.C = C_pad; q.F = 1; q.KH = KH; q.KW = KW;
     q.pad_h = pad_h; q.pad_w = pad_w;
     q.e_min = -pad_w * C_pad; q.e_max = (KW - pad_w) * C_pad; q.kwin = q.e_max - q.e_min;
-    q.in_row = W * C_pad; q.out_row = (int)(W_out * C_out); q.M = M_pad;
+    q.in_row = W * C_pad; q.out_row = (int)(W_out * Co_pad); q.M = M_pad;
     q.cgcd = 8; q.cJ = KW * C_pad / 8;
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
     s.padded_kernel = fc_choose_kernel(q, dtype);
 
     const long long xpad_bytes = (long long)N * H * W * C_pad * eb;
-    const long long wpad_bytes = (long long)KH * KW * C_pad * C_out * eb;
+    const long long wpad_bytes = (long long)KH * KW * C_pad * Co_pad * eb;
+    const long long ypad_bytes = Co_pad == C_out ? 0 : (long long)N * H_out * W_out * Co_pad * eb;
     s.workspace_bytes = s.conv_kernel == FC_KERNEL_GATHER ? 0 : (long long)align_up((size_t)s.w_exp_bytes, 256);
     // Compact filter: one zero-padded copy of the KW*C_in x C_out tap matrix per kh and per chunk
     // phase for the vector kernels; the gather kernel reads the original filter as it is.
@@ -126,8 +131,9 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     p->ws_xpad = 0;
     p->ws_wpad = align_up((size_t)xpad_bytes, 256);
     p->ws_wpack = p->ws_wpad + align_up((size_t)wpad_bytes, 256);
-    s.padded_workspace_bytes =
-        (long long)(p->ws_wpack + (s.padded_kernel == FC_KERNEL_GATHER ? 0 : align_up((size_t)wpad_bytes, 256)));
+    p->ws_bpad = p->ws_wpack + (s.padded_kernel == FC_KERNEL_GATHER ? 0 : align_up((size_t)wpad_bytes, 256));
+    p->ws_ypad = p->ws_bpad + align_up((size_t)Co_pad * eb, 256);
+    s.padded_workspace_bytes = (long long)(p->ws_ypad + align_up((size_t)ypad_bytes, 256));
 
     const bool mfma16 = dtype != FOLDCONV_F32;
     const int kstep = mfma16 ? 16 : 2;
