@@ -25,9 +25,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the folded convolution on the headline layer from rocprofv3 counters
-# (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 1.000 + FETCH_SIZE x 1.997).  Set to None whenever
+# (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 0.999 + FETCH_SIZE x 1.998).  Set to None whenever
 # the convolution kernel changes after the counters were taken.
-MEASURED_TRAFFIC_BYTES = 431.9e6
+MEASURED_TRAFFIC_BYTES = 431.3e6
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 
 
@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only; --gpus N with N > 1 is not supported "
+        print("bench.py: libfoldconv is measured on one GPU only; --gpus N with N > 1 is not supported "
               "(the path shards over the batch without collectives).", file=sys.stderr)
         sys.exit(2)
 
