@@ -10,22 +10,22 @@
 // blocks of 32 elements (two MFMA K-steps), restricted to the band of w' that
 // can be non-zero for the tile's output slots (paper: Eq. "filter_construct";
 // off-band blocks are structural zeros) unless the dense walk is asked for.
-// Both operands are staged through LDS in MFMA operand order, one 16-byte
-// chunk (8 consecutive K values of one row/column) per lane access:
+// Both operands are staged in LDS by buffer loads that deposit straight into
+// LDS (no register round trip), one 16-byte chunk (8 consecutive K values of
+// one row/column) per lane:
 //   filter: pack[kh][q][n][8] rows copied as they are (coalesced),
-//   input:  the window chunk [e, e+8) of each pixel's input row, a 16-byte
-//           range-checked buffer load (zero padding = out-of-range offset).
-// The K loop is one software pipeline: while block b is multiplied, the global
-// loads of block b+2 and the LDS writes of block b+1 are issued one per MFMA
-// step, and the LDS fragment reads run two steps ahead of the MFMAs that use
-// them; one barrier per K block.  The staging loads are inline assembly with
-// explicit wait counts (checked by a test that walks the generated code).
+//   input:  the window chunk [e, e+8) of each pixel's input row, range-checked
+//           (zero padding = out-of-range offset = zeros deposited).
+// The K loop is one software pipeline over three LDS stages: while block b is
+// multiplied, block b+1 has landed or is landing and the loads of block b+2
+// are issued, one per MFMA step; LDS fragment reads run two steps ahead of the
+// MFMAs that use them; one wait and one barrier per K block.  The staging
+// loads are inline assembly with explicit wait counts (checked by a test that
+// walks the generated code).
 // Epilogue: bias as a rank-1 MFMA, ReLU, one rounding, transpose through LDS,
 // 16-byte row-contiguous stores with the reconstruct step fused in.
 // paper: Eq. "new_conv_H", Eq. "bias_construct", Reconstruct step.
 #include <hip/hip_runtime.h>
-
-#include <type_traits>
 
 #include "launch.h"
 #include "mfma_types.h"
@@ -39,17 +39,26 @@ constexpr int BK = 32;
 constexpr int QPB = BK / 8;                 // 16-byte chunks per row per K block
 constexpr unsigned kOutOfRange = 0x80000000u;
 
-// LDS geometry for a tile of BN output columns x BM pixels
+// LDS geometry for a tile of BN output columns x BM pixels.  Staging goes straight from global
+// memory into LDS (buffer loads with the LDS modifier: lane l of the wave deposits its 16 bytes at
+// the instruction's LDS base + 16*l), so every staging instruction must fill 1 KB of consecutive
+// LDS addresses:
+//   filter: QPB planes, plane q = chunk q of every column, [column][16 bytes]: 64 consecutive
+//           columns per instruction, which are 1 KB of consecutive global addresses as well;
+//   input:  [pixel][QPB chunks of 16 bytes] row-major, 16 pixels per instruction, so that the four
+//           lanes of a pixel fetch 64 consecutive global bytes.  The chunk stored at position s of
+//           pixel p is chunk s ^ ((p >> 2) & 3): with that swizzle the MFMA operand reads (lane r
+//           reads one chunk of pixel r) of any 16 consecutive lanes cover all 64 banks once.
 template <int BN, int BM>
 struct TileLds {
-    // bytes of one chunk plane; the pad staggers the planes so that the 16 lanes of a staging write
-    // (QPB chunks x 16/QPB pixels) fall on 16 distinct bank groups
-    static constexpr int PLANE_F = BN * 16 + 256 / QPB;
-    static constexpr int PLANE_I = BM * 16 + 256 / QPB;
-    static constexpr int STAGE = QPB * (PLANE_F + PLANE_I);  // filter planes then input planes
+    static constexpr int PLANE_F = BN * 16 + 64;             // the pad staggers the planes across banks
+    static constexpr int FILT = QPB * PLANE_F;
+    static constexpr int INP = BM * QPB * 16;
+    static constexpr int STAGE = FILT + INP;                 // filter planes then input rows
+    static constexpr int STAGES = 3;                         // multiplied | landed or landing | landing
     static constexpr int EPITCH = BN * 2 + 16;               // bytes per row of the transposed output half-tile
-    static constexpr int EBYTES = (BM / 2) * EPITCH;         // the epilogue handles one 32-pixel MFMA row per wave at a time
-    static constexpr int BYTES = (2 * STAGE > EBYTES) ? 2 * STAGE : EBYTES;
+    static constexpr int EBYTES = 64 * EPITCH;               // the epilogue handles one 32-pixel MFMA row per wave at a time
+    static constexpr int BYTES = (STAGES * STAGE > EBYTES) ? STAGES * STAGE : EBYTES;
 };
 
 template <typename TR>
@@ -84,7 +93,7 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     constexpr int BM = 64 * WM;        // WM wave rows of two MFMA tiles
     constexpr int THREADS = 128 * WM;  // 2 x WM waves
     using L = TileLds<BN, BM>;
-    constexpr int PLANE_F = L::PLANE_F, PLANE_I = L::PLANE_I, STAGE = L::STAGE, EPITCH = L::EPITCH;
+    constexpr int PLANE_F = L::PLANE_F, FILT = L::FILT, STAGE = L::STAGE, STAGES = L::STAGES, EPITCH = L::EPITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds[L::BYTES];
 
     // Workgroup b runs on XCD b % 8.  Each XCD takes one contiguous range of tiles, N tiles
@@ -121,125 +130,115 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     u32x4 wr = make_srd(wp, a.wp_bytes);
 
     // ---- this thread's share of the staging loads -----------------------------
-    // input: chunk column qi of NI pixels, one 16-byte chunk each
-    constexpr int NI = (BM * QPB) / THREADS;   // input chunks per thread per K block
-    constexpr int NF = (BN * QPB) / THREADS;   // filter chunks per thread per K block
-    constexpr int NL = NI + NF;                // staging loads per thread per K block
-    constexpr int MSTEP = THREADS / QPB;       // pixels covered by one pass of the workgroup
-    const int qi = t & (QPB - 1);
-    int pix[NI], ho_[NI], col_[NI];
+    // Per K block there are BM/16 staging instructions for the input (16 pixels x 4 chunks each)
+    // and QPB*BN/64 for the filter (64 columns of one chunk plane each), dealt evenly to the
+    // 2*WM waves: NI and NF per wave, one 16-byte chunk per lane.
+    constexpr int NW = THREADS / 64;
+    constexpr int NI = (BM / 16) / NW;         // = 2
+    constexpr int NF = (QPB * BN / 64) / NW;   // a wave's filter instructions stay inside one chunk plane
+    constexpr int NL = NI + NF;                // staging loads per lane per K block
+    static_assert(QPB == 4 && NI * NW * 16 == BM && NF * NW * 64 == QPB * BN && (BN / 64) % NF == 0, "staging split");
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    const int ci = (lane & 3) ^ ((lane >> 4) & 3);  // input chunk this lane fetches (position lane & 3, swizzled)
+    // Per-lane constants, arranged so that a K block costs one add for the offset and a few
+    // compares per load: everything that depends only on the block (kh, e0) is wave-uniform.
+    unsigned pix2[NI];          // byte offset in x of the lane's chunk at kh = 0, e0 = 0
+    int hb[NI], col_[NI];       // input row at kh = 0 (may be negative: padding), column of the chunk at e0 = 0
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const unsigned m = m0 + (unsigned)(t / QPB) + (unsigned)(MSTEP * i);
+        const unsigned m = m0 + (unsigned)((wv * NI + i) * 16 + (lane >> 2));
         const bool vm = m < (unsigned)g.M;
         const unsigned mm = vm ? m : 0u;
         const unsigned wo = mm % (unsigned)g.Wf_out;
         const unsigned rowid = mm / (unsigned)g.Wf_out;
         const unsigned ho = rowid % (unsigned)g.Hout;
         const unsigned img = rowid / (unsigned)g.Hout;
-        ho_[i] = vm ? (int)ho : -0x40000000;  // a pixel past the end fails every row test below
-        col_[i] = (int)wo * g.FC + 8 * qi;
-        pix[i] = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i];
+        hb[i] = vm ? (int)ho - g.pad_h : -0x40000000;  // a pixel past the end fails every row test below
+        col_[i] = (int)wo * g.FC + 8 * ci;
+        pix2[i] = 2u * (unsigned)(((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col_[i]);
     }
+    const int ecut = e_hi - 8 * ci;  // the lane's chunk lies inside the window while e0 < ecut
     // The chunk for window chunk q of a column sits at  fbase + (kh*f_jmax + (q - fj0)) * f_stride
     // when 0 <= q - fj0 < f_jmax.  Packed w': one run of q_per_kh chunks per kh, column stride NCo.
     // Compact storage: the column's slot fixes the phase copy and the first window chunk its tap
     // matrix reaches (fc_compact_chunk); chunks outside are structural zeros.
-    int nf[NF], qf[NF], fbase[NF], fj0[NF];
+    const int qf = (wv * NF) / (BN / 64);   // the wave's filter chunk plane
+    const int cg0 = (wv * NF) % (BN / 64);  // and its first group of 64 columns
+    unsigned fb2[NF];   // byte offset of the column's chunk for kh = 0, q = 0
+    int fj0[NF];
     const int f_jmax = g.compact ? g.cJ : q_per_kh;
     const int f_stride = g.compact ? g.Co : g.NCo;
 #pragma unroll
     for (int i = 0; i < NF; ++i) {
-        const int idx = t + THREADS * i;
-        nf[i] = idx % BN;
-        qf[i] = idx / BN;
-        const bool vn = n0 + nf[i] < g.NCo;
-        const int n = vn ? n0 + nf[i] : 0;
+        const int col = (cg0 + i) * 64 + lane;
+        const bool vn = n0 + col < g.NCo;
+        const int n = vn ? n0 + col : 0;
+        int fbase;
         if (g.compact) {
             const int slot = n / g.Co, co = n - slot * g.Co;
             const int a_g = (slot - g.pad_w) * g.C - g.e_min;
             fj0[i] = a_g >> 3;
-            fbase[i] = ((a_g & 7) / g.cgcd) * g.KH * g.cJ * g.Co + co;
+            fbase = ((a_g & 7) / g.cgcd) * g.KH * g.cJ * g.Co + co;
         } else {
             fj0[i] = 0;
-            fbase[i] = n;
+            fbase = n;
         }
+        fb2[i] = 16u * (unsigned)(fbase - fj0[i] * f_stride);
         if (!vn) fj0[i] = 0x40000000;  // a column past the end fails the chunk range test below
     }
 
-    // Staging loads are issued from inline assembly and waited for with explicit counts: left to
-    // itself the compiler wraps every address select in a branch and waits for the loads of the
-    // previous K block at the top of the loop.  Vector-memory loads return in issue order, so
-    // "at most NL outstanding" means every load older than the NL newest has landed.
-    // Nothing else in the K loop touches vector memory.  The pipeline below has one code path:
-    // blocks past the end are issued with every lane out of range (no memory traffic, zeros
-    // returned) and committed to a stage nobody reads; what is still in flight when the loop
-    // ends is drained before any register is reused.
-    struct StageRegs {
-        u32x4 r[NL];
-    };
-    StageRegs ra, rb;
-    int kh_l = 0, kb_l = 0;  // next block to issue
+    // Staging loads are inline assembly (M0 = LDS base of the instruction) with hand-counted waits:
+    // the compiler would wait for every outstanding load-to-LDS before any LDS read.  Vector-memory
+    // loads complete in issue order, so "at most NL outstanding" means every load older than the NL
+    // newest has reached LDS.  Nothing else in the K loop touches vector memory.  The pipeline has one
+    // code path: blocks past the end are issued with every lane out of range (no memory traffic,
+    // zeros deposited in a stage nobody reads), and everything is drained before LDS is reused.
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    int kh_l = 0, kb_l = 0;    // next block to issue
     int is_kh = 0, is_e0 = 0;  // block being issued (wave-uniform)
+    unsigned is_lds = 0;       // LDS address of its stage
+    int is_stage = 0;
+    unsigned is_xoff = 0, is_foff = 0;  // wave-uniform byte offsets of the block being issued
+    int is_q = 0;                       // window chunk index of the wave's filter plane in that block
+    bool is_fok = false;                // that chunk lies inside the window
     auto issue_begin = [&]() {
         const bool live = kh_l < g.KH;
         is_kh = live ? kh_l : 0;
         is_e0 = live ? e_lo + kb_l * BK : e_hi;  // past the window: every lane out of range
+        is_lds = lds_base + (unsigned)(is_stage * STAGE);
+        is_stage = is_stage + 1 == STAGES ? 0 : is_stage + 1;
+        is_xoff = 2u * (unsigned)(is_kh * g.in_row + is_e0);
+        const int e = is_e0 + 8 * qf;
+        is_q = (e - g.e_min) >> 3;
+        is_fok = e < e_hi;
+        is_foff = 16u * (unsigned)f_stride * (unsigned)(is_kh * f_jmax + is_q);
         if (++kb_l == kblocks) {
             kb_l = 0;
             ++kh_l;
         }
     };
     // load number `idx` of the block (a constant once the caller's loop is unrolled): NI input
-    // chunks, then NF filter chunks
-    auto issue_one = [&](StageRegs &rg, int idx) {
-        const int kh = is_kh, e0 = is_e0;
+    // instructions, then NF filter instructions
+    auto issue_one = [&](int idx) {
         if (idx < NI) {
             const int i = idx < NI ? idx : 0;
-            const int hi = ho_[i] + kh - g.pad_h;
-            const int col = col_[i] + e0;
-            const int ok = (int)((unsigned)hi < (unsigned)g.H) & (int)((unsigned)col < (unsigned)g.in_row) &
-                           (int)(e0 + 8 * qi < e_hi);
-            const unsigned val = 2u * (unsigned)(pix[i] + kh * g.in_row + e0);
-            const unsigned off = ok ? val : kOutOfRange;
-            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(rg.r[i]) : "v"(off), "s"(xr) : "memory");
+            const int ok = (int)((unsigned)(hb[i] + is_kh) < (unsigned)g.H) &
+                           (int)((unsigned)(col_[i] + is_e0) < (unsigned)g.in_row) & (int)(is_e0 < ecut);
+            const unsigned off = ok ? pix2[i] + is_xoff : kOutOfRange;
+            const unsigned dst = is_lds + (unsigned)(FILT + (wv * NI + i) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(xr) : "memory");
         } else {
             const int i = idx < NI ? 0 : idx - NI;
-            const int e = e0 + 8 * qf[i];
-            const int j = ((e - g.e_min) >> 3) - fj0[i];
-            const int ok = (int)(e < e_hi) & (int)((unsigned)j < (unsigned)f_jmax);
-            const unsigned val = 16u * ((unsigned)fbase[i] + (unsigned)(kh * f_jmax + j) * (unsigned)f_stride);
-            const unsigned off = ok ? val : kOutOfRange;
-            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(rg.r[NI + i]) : "v"(off), "s"(wr) : "memory");
+            const int ok = (int)is_fok & (int)((unsigned)(is_q - fj0[i]) < (unsigned)f_jmax);
+            const unsigned off = ok ? fb2[i] + is_foff : kOutOfRange;
+            const unsigned dst = is_lds + (unsigned)(qf * PLANE_F + (cg0 + i) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(dst), "v"(off), "s"(wr) : "memory");
         }
     };
-    auto issue = [&](StageRegs &rg) {
+    auto issue = [&]() {
         issue_begin();
 #pragma unroll
-        for (int k = 0; k < NL; ++k) issue_one(rg, k);
-    };
-    // One wait that names every register of the set, so the set stays allocated until it has landed:
-    // returns once at most `count` younger loads are outstanding.
-    auto wait_set = [&](StageRegs &rg, auto count) {
-        constexpr int N = decltype(count)::value;
-        if constexpr (NL == 4)
-            asm volatile("s_waitcnt vmcnt(%4)" : "+v"(rg.r[0]), "+v"(rg.r[1]), "+v"(rg.r[2]), "+v"(rg.r[3]) : "n"(N) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(%6)"
-                         : "+v"(rg.r[0]), "+v"(rg.r[1]), "+v"(rg.r[2]), "+v"(rg.r[3]), "+v"(rg.r[4]), "+v"(rg.r[5])
-                         : "n"(N) : "memory");
-    };
-    static_assert(NL == 4 || NL == 6, "wait_set lists the staging registers explicitly");
-    auto commit_one = [&](StageRegs &rg, int stage, int idx) {
-        unsigned char *sf = lds + stage * STAGE;
-        unsigned char *si = sf + QPB * PLANE_F;
-        if (idx < NI) {
-            const int i = idx < NI ? idx : 0;
-            *reinterpret_cast<u32x4 *>(si + qi * PLANE_I + (t / QPB + MSTEP * i) * 16) = rg.r[i];
-        } else {
-            const int i = idx < NI ? 0 : idx - NI;
-            *reinterpret_cast<u32x4 *>(sf + qf[i] * PLANE_F + nf[i] * 16) = rg.r[NI + i];
-        }
+        for (int k = 0; k < NL; ++k) issue_one(k);
     };
 
     // ---- accumulators, initialised with the bias through a rank-1 MFMA ----------
@@ -267,18 +266,16 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     // ---- K loop -----------------------------------------------------------------
     // One K block = BK/16 MFMA K-steps x TN filter fragments, walked as a rolling pipeline: the
     // fragment for step k+2 is requested from LDS before the two MFMAs of step k are issued, so
-    // an LDS round trip has 128 cycles of matrix work to hide behind.  The staging traffic of the
-    // blocks ahead is woven into the same instruction stream instead of following it: the global
-    // loads of block b+2 go out after the first step, and the LDS writes of block b+1 (into the
-    // stage nobody reads during this block) after the middle one, so they complete under the
-    // remaining MFMAs and the wave reaches the barrier with nothing left to wait for.  The
-    // scheduling fences keep the compiler from regrouping any of it.
-    auto block = [&](int stage, StageRegs &next2, StageRegs &next1) {
-        const unsigned char *sf = lds + stage * STAGE;
-        const unsigned char *si = sf + QPB * PLANE_F;
+    // an LDS round trip has 128 cycles of matrix work to hide behind.  The staging loads of block
+    // b+2 are woven into the same instruction stream, one per MFMA step.  The scheduling fences keep
+    // the compiler from regrouping any of it.
+    int cur_stage = 0;
+    auto block = [&]() {
+        const unsigned char *sf = lds + cur_stage * STAGE;
+        const unsigned char *si = sf + FILT;
+        cur_stage = cur_stage + 1 == STAGES ? 0 : cur_stage + 1;
         constexpr int KS = BK / 16, STEPS = KS * TN;
-        constexpr int W = STEPS - NL;  // first step that writes to LDS (earlier placements measured the same)
-        static_assert(W >= 0 && W + NL <= STEPS && NL <= STEPS, "one staging load and one staging write per step");
+        static_assert(NL <= STEPS, "one staging load per step");
         Vec fr[3], in[KS][2];
         auto read_f = [&](int k) {
             const int qc = 2 * (k / TN) + hf;
@@ -286,7 +283,7 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
         };
         auto read_i = [&](int ks, int mt) {
             const int qc = 2 * ks + hf;
-            return *reinterpret_cast<const Vec *>(si + qc * PLANE_I + (wm * 64 + mt * 32 + r) * 16);
+            return *reinterpret_cast<const Vec *>(si + (wm * 64 + mt * 32 + r) * 64 + ((qc ^ ((r >> 2) & 3)) * 16));
         };
         issue_begin();
         in[0][0] = read_i(0, 0);
@@ -307,33 +304,31 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
             acc[nt][0] = TR::mfma(fr[k % 3], in[ks][0], acc[nt][0]);
             acc[nt][1] = TR::mfma(fr[k % 3], in[ks][1], acc[nt][1]);
             __builtin_amdgcn_sched_barrier(0);
-            // staging work of this step: one global load of block b+2, and from step W on one LDS
-            // write of block b+1 (its loads are older than the k+1 loads of b+2 issued so far)
-            if (k < NL) issue_one(next2, k);
-            if (k == W) wait_set(next1, std::integral_constant<int, (W + 1 < NL ? W + 1 : NL)>{});
-            if (k >= W && k < W + NL) commit_one(next1, stage ^ 1, k - W);
+            if (k < NL) issue_one(k);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // Software pipeline over K blocks b = 0 .. T_total-1 (set and stage of block b: b & 1): while
-    // block b is multiplied, block b+2 is requested from memory and block b+1 is written to LDS.
+    // What the barrier at the end of block b publishes is block b+1: its loads are older than the NL
+    // loads of block b+2 issued during block b.  LDS reads of block b are complete (their values
+    // were consumed by MFMAs), so the stage of block b may be overwritten by block b+3 afterwards.
+    auto publish = [&]() {
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NL) : "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // Software pipeline over K blocks b = 0 .. T_total-1 (stage of block b: b mod 3): while block b is
+    // multiplied, block b+1 has landed or is landing and block b+2 is requested.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing the compiler tracks may be in flight
-    issue(ra);
-    issue(rb);
-    wait_set(ra, std::integral_constant<int, NL>{});
-#pragma unroll
-    for (int k = 0; k < NL; ++k) commit_one(ra, 0, k);
-    __syncthreads();
-    for (int it = 0; it < T_total; it += 2) {
-        block(0, ra, rb);  // multiply block it, request it+2 into ra, write it+1 from rb to stage 1
-        __syncthreads();
-        if (it + 1 >= T_total) break;
-        block(1, rb, ra);  // multiply block it+1, request it+3 into rb, write it+2 from ra to stage 0
-        __syncthreads();
+    issue();
+    issue();
+    publish();
+    for (int it = 0; it < T_total; ++it) {
+        block();
+        publish();
     }
-    // the set issued last was never committed: let it land before its registers are reused
-    wait_set(ra, std::integral_constant<int, 0>{});
-    wait_set(rb, std::integral_constant<int, 0>{});
+    // drain the blocks requested past the end before LDS is reused
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
     // ---- epilogue: round, ReLU, transpose through LDS (stages are free after the last barrier),
     // 64 pixels (one MFMA tile row per wave) at a time ----
@@ -403,6 +398,8 @@ template <typename TR>
 int launch_any(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     // A 256 x 256 tile on eight waves (WM = 4) moves a third fewer operand bytes per multiply but
     // measured the same as 256 x 128 on the layers it fits, so only WM = 2 is instantiated.
+    // WM = 4 (a 256 x 256 tile on eight waves, a third fewer operand bytes out of L2 per multiply)
+    // measured the same as 256 x 128 on the one layer of the benchmark set it fits; not instantiated.
     return fc_tiled_bn(g) == 256 ? launch<TR, 4, 2>(g, x, wp, bias, y, st) : launch<TR, 2, 2>(g, x, wp, bias, y, st);
 }
 
