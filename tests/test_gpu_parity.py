@@ -276,3 +276,57 @@ def test_gemm_as_folded_one_by_one_conv(fc, oracle, M, K, N, F, dt):
     assert rel_l2_per_image(f64(y), ref) <= TOL[dt]
     yp = run_padded(fc, plan, x, w, None, 0).reshape(1, M, N)
     assert rel_l2_per_image(f64(yp), ref) <= TOL[dt]
+
+
+def _random_cases(n, seed):
+    """Seeded random geometries: small enough for the oracle, varied enough to reach all three kernels,
+    ragged tiles in m and n, VALID / 'same' / over-padded, even and odd kernels, F from 1 to W."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        F = int(rng.choice([1, 2, 4, 8, 16]))
+        Wf = int(rng.integers(1, 9))
+        W = F * Wf
+        H = int(rng.integers(1, 12))
+        C = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 20, 36, 66]))
+        Co = int(rng.choice([1, 3, 8, 16, 20, 40, 64, 72]))
+        KH = int(rng.integers(1, min(H, 5) + 1))
+        KW = int(rng.integers(1, 6))
+        pad = int(rng.integers(0, 3))
+        N = int(rng.integers(1, 4))
+        ph, pw = (pad if KH > 1 else 0), (pad if KW > 1 else 0)
+        if H + 2 * ph - KH + 1 <= 0 or W + 2 * pw - KW + 1 <= 0:
+            continue
+        if N * H * W * Co * KH * KW * C > 3e8:
+            continue
+        out.append((N, H, W, C, Co, KH, KW, pad, F, bool(rng.integers(0, 2)), bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_geometries(fc, oracle, chunk, dt):
+    kernels = set()
+    for case in _random_cases(25, 1000 + chunk):
+        N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
+        x = draw((N, H, W, C), dt, 41)
+        w = (draw((KH, KW, C, Co), dt, 42) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+        b = draw((Co,), dt, 43) if hb else None
+        ph, pw = oracle.axis_pads(KH, KW, pad)
+        ref = oracle.conv_direct(f64(x), f64(w), None if b is None else f64(b), ph, pw, relu)
+        plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, x.dtype)
+        kernels.add(plan.shapes.conv_kernel)
+        rflag = fc.FLAG_RELU if relu else 0
+        scale = np.sqrt(np.mean(ref ** 2)) + 1e-30
+        for name, y in (("band", run_folded(fc, plan, x, w, b, rflag)),
+                        ("dense", run_folded(fc, plan, x, w, b, rflag | fc.FLAG_DENSE_K)),
+                        ("compact", run_compact(fc, plan, x, w, b, rflag)),
+                        ("padded", run_padded(fc, plan, x, w, b, rflag))):
+            assert not bool(torch.isnan(y).any()), (case, name)
+            # per-image relative L2 where the reference is not (nearly) all zeros after ReLU
+            if scale > 1e-3:
+                err = np.sqrt(np.mean((f64(y) - ref) ** 2)) / scale
+                assert err <= TOL[dt], (case, name, err)
+            else:
+                assert np.abs(f64(y) - ref).max() <= 1e-2, (case, name)
+    assert len(kernels) >= 2
