@@ -200,10 +200,22 @@ def main():
         stack = runner.FoldedStack(l5, w5, b5)
         x5d = x5.cuda()
         flops5 = sum(L5.plan.shapes.useful_flops for L5 in stack.layers)
-        _, s_ms = time_events(lambda: stack.forward(x5d), 10, 2)
-        _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 10, 2)
-        _, sc_ms = time_events(lambda: stack.forward(x5d, compact=True), 10, 2)
+        _, s_ms = time_events(lambda: stack.forward(x5d), 20, 15)  # long warm-up: the first launches after idling run slower
+        _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 20, 5)
+        _, sc_ms = time_events(lambda: stack.forward(x5d, compact=True), 20, 5)
+        # the same five launches replayed from a captured HIP graph (no per-launch host work)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            stack.forward(x5d, compact=True)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            stack.forward(x5d, compact=True)
+        _, sg_ms = time_events(graph.replay, 20, 5)
         extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "folded_compact_filter_ms": sc_ms,
+                              "folded_compact_filter_graph_ms": sg_ms,
                               "filter_bytes": {"expanded": sum(int(L5.plan.shapes.w_exp_bytes) for L5 in stack.layers),
                                                "compact": sum(int(L5.plan.shapes.filter_compact_bytes) for L5 in stack.layers)},
                               "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,

@@ -95,3 +95,36 @@ def test_output_beyond_four_gigabytes(env, oracle):
     for r0 in range(0, M, 1 << 24):
         assert not bool(torch.isnan(y[r0:r0 + 4096]).any()), r0
     assert not bool(torch.isnan(y[-4096:]).any())
+
+
+def test_stack_replays_from_a_captured_graph(env):
+    """The library allocates nothing and never synchronises, so a whole stack of layers can be
+    captured into a HIP graph.  Every replay (with eager work and synchronisations in between, and
+    with new input data copied into the captured buffer) must reproduce the eager result bit for bit."""
+    fc, runner, wl = env
+    layers, x, ws, bs = wl.make_config("c5", N=2)
+    stack = runner.FoldedStack(layers, ws, bs)
+    xs = [x, torch.flip(x, dims=[2]).contiguous(), (x * 0.5).contiguous()]
+    eager = []
+    for xi in xs:
+        y = stack.forward(xi.cuda())
+        torch.cuda.synchronize()
+        eager.append(y.clone())
+    x_static = xs[0].cuda().clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        stack.forward(x_static)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        y_static = stack.forward(x_static)
+    for rep in range(2):
+        for xi, want in zip(xs, eager):
+            x_static.copy_(xi.cuda())
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_static, want), rep
+            y_static.add_(1.0)                       # eager work between replays; the next replay must overwrite it
