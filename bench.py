@@ -221,6 +221,41 @@ def main():
                               "useful_tflops": flops5 / (s_ms * 1e-3) / 1e12,
                               "useful_pct_of_mfma_peak": 100.0 * flops5 / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                               "kernels": [["gather", "tiled", "stream"][L5.plan.shapes.conv_kernel] for L5 in stack.layers]}
+        # the small configurations (parity-test cases, not the headline): 20 launches replayed from a
+        # captured graph so that the per-launch host work of the Python binding is not what is timed
+        small = {}
+        for cname in ("c1", "c3", "c4"):
+            ls, xs_, ws_, bs_ = wl.make_config(cname)
+            Ls = runner.FoldedLayer(ls[0], ws_[0], bs_[0])
+            xsd = xs_.cuda()
+            ys = Ls.new_output()
+            ss = Ls.plan.shapes
+
+            def burst(padded=False):
+                for _ in range(20):
+                    if padded:
+                        Ls.forward_padded(xsd, ys)
+                    else:
+                        Ls.forward(xsd, ys)
+
+            res = {}
+            for key, padded in (("folded_us", False), ("padded_us", True)):
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    burst(padded)
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr):
+                    burst(padded)
+                _, b_ms = time_events(gr.replay, 10, 3)
+                res[key] = b_ms * 1e3 / 20
+            res["useful_tflops"] = ss.useful_flops / (res["folded_us"] * 1e-6) / 1e12
+            res["GBps"] = (ss.x_bytes + ss.y_bytes + ss.w_exp_bytes) / (res["folded_us"] * 1e-6) / 1e9
+            res["kernel"] = ["gather", "tiled", "stream"][ss.conv_kernel]
+            small[cname] = res
+        extras["small_configs"] = small
         # tall-skinny GEMM as a folded 1x1 convolution: A[2^21, 12] x B[12, 64], fp16, F = 4
         Mg, Kg, Ng, Fg = 1 << 21, 12, 64, 4
         gp = fc.foldconv_plan_gemm(Mg, Kg, Ng, Fg, torch.float16)
