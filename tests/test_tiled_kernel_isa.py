@@ -122,6 +122,9 @@ def test_staging_loads_are_published_with_the_right_counts(asm):
         waits = [int(w) for l in lines for w in re.findall(r"s_waitcnt vmcnt\((\d+)\)$", l)]
         assert 0 in waits and waits.count(nl) >= 2, (name, waits)
         assert explore(lines, name, nl) > 10
+        # M0 is written by the inline assembly without the compiler knowing: nothing else may use it
+        others = [l for l in lines if re.search(r"\bm0\b", l) and not l.startswith("s_mov_b32 m0,")]
+        assert not others, (name, others[:3])
 
 
 @pytest.mark.parametrize("mutation", ["drop_wait", "weak_wait", "no_drain", "no_m0"])
