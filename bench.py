@@ -105,6 +105,15 @@ def main():
     algo_bytes = s.x_bytes + s.w_exp_bytes + s.bias_bytes + s.y_bytes  # x + packed w' + b read once, y written once
     achieved_gbs = algo_bytes / (dev_ms * 1e-3) / 1e9
 
+    # per-launch distribution (one event pair per launch, after the timed region): median and minimum
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.steps, 50))]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_launch = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+
     out = {
         "metric": "useful conv TFLOP/s (fold vs zero-pad) + % MFMA peak, C_in=3 224^2 3x3 fp16",
         "value": useful_tflops,
@@ -129,6 +138,8 @@ def main():
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES,
             "kernel_ms": dev_ms,
+            "kernel_ms_median": per_launch[len(per_launch) // 2],
+            "kernel_ms_min": per_launch[0],
             "algorithmic_bytes": algo_bytes,
         },
         "useful_pct_of_mfma_peak": 100.0 * useful_tflops / MFMA_PEAK_TFLOPS,

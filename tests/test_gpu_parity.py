@@ -330,3 +330,27 @@ def test_random_geometries(fc, oracle, chunk, dt):
             else:
                 assert np.abs(f64(y) - ref).max() <= 1e-2, (case, name)
     assert len(kernels) >= 2
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,H,W,C,Co,KH,KW,pad", [(2, 9, 12, 8, 16, 3, 3, 1), (1, 6, 40, 16, 64, 1, 5, 2), (1, 7, 7, 64, 40, 3, 3, 0)])
+def test_fold_factor_one_is_the_direct_path(fc, oracle, N, H, W, C, Co, KH, KW, pad, dt):
+    """F = 1: the fold is the identity, the expanded filter is the filter itself, and with C_in
+    already aligned the zero-padded reference pads nothing: both entry points must then produce the
+    same bits (same kernel, same operands)."""
+    x = draw((N, H, W, C), dt, 51)
+    w = (draw((KH, KW, C, Co), dt, 52) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+    b = draw((Co,), dt, 53)
+    plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, 1, x.dtype)
+    s = plan.shapes
+    assert (s.W_fold, s.C_fold, s.KW_fold, s.C_pad, s.C_out_pad) == (W, C, KW, C, Co)
+    w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=x.dtype, device="cuda")
+    fc.foldconv_expand_filter(plan, w.cuda(), w_exp)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(w_exp).reshape(-1), bits(w).reshape(-1))
+    y_f = run_folded(fc, plan, x, w, b, fc.FLAG_RELU)
+    y_p = run_padded(fc, plan, x, w, b, fc.FLAG_RELU)
+    assert np.array_equal(bits(y_f), bits(y_p))
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    ref = oracle.conv_direct(f64(x), f64(w), f64(b), ph, pw, True)
+    assert rel_l2_per_image(f64(y_f), ref) <= TOL[dt]
