@@ -310,6 +310,18 @@ def main():
             nchw[axis_name] = {"total_ms": n_ms, "fold_ms": nf_ms, "unfold_ms": nu_ms,
                                "unfold_GBps": 2 * sn.y_bytes / (nu_ms * 1e-3) / 1e9,
                                "useful_tflops": sn.useful_flops / (n_ms * 1e-3) / 1e12}
+            if sn.out_nchw_fused:
+                # the convolution writes y channels-first itself: no folded output, no reconstruct pass
+                def step_fused():
+                    fc.foldconv_fold_input_nchw(pn, xn, xf_n)
+                    fc.foldconv_forward(pn, xf_n, w_exp_n, bn, yn, ws_n, fc.FLAG_OUT_NCHW | fc.FLAG_FILTER_PACKED)
+
+                _, fz_ms = time_events(step_fused, 20, 5)
+                _, fk_ms = time_events(lambda: fc.foldconv_forward(pn, xf_n, w_exp_n, bn, yn, ws_n,
+                                                                   fc.FLAG_OUT_NCHW | fc.FLAG_FILTER_PACKED), 20, 5)
+                nchw[axis_name].update({"fused_total_ms": fz_ms, "fused_forward_ms": fk_ms,
+                                        "fused_forward_GBps": (sn.x_bytes + sn.y_bytes) / (fk_ms * 1e-3) / 1e9,
+                                        "fused_useful_tflops": sn.useful_flops / (fz_ms * 1e-3) / 1e12})
             del w_exp_n, ws_n, xf_n, yn
         extras["nchw"] = nchw
         out["extras"] = extras

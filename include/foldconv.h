@@ -66,9 +66,13 @@ enum {
     FOLDCONV_FLAG_FILTER_PACKED = 8u, /* workspace already holds the packed filter written by a
                                          previous call with the same plan and the same filter
                                          (weights are static after training): skip re-packing  */
-    FOLDCONV_FLAG_FILTER_COMPACT = 16u /* workspace holds the compact filter written by
+    FOLDCONV_FLAG_FILTER_COMPACT = 16u, /* workspace holds the compact filter written by
                                          foldconv_pack_filter_compact (only the non-zero blocks
                                          of w'); w_exp is not read and may be NULL              */
+    FOLDCONV_FLAG_OUT_NCHW = 32u      /* write y channels-first, [N][C_out][H_out][W_out], in the
+                                         same launch (no y' round trip through memory).  Only
+                                         where shapes.out_nchw_fused is 1, else
+                                         FOLDCONV_ERR_UNSUPPORTED; excludes KEEP_FOLDED          */
 };
 
 /* Which image axis of a channels-first (NCHW) tensor is folded into the channels. */
@@ -95,6 +99,10 @@ typedef struct foldconv_shapes_s {
     int32_t fold_axis;              /* FOLDCONV_FOLD_W; FOLDCONV_FOLD_H for a plan made by
                                        foldconv_plan_nchw with height folding: then H, W, KH, KW
                                        and the *_out fields above describe the transposed image */
+    int32_t out_nchw_fused;         /* 1 when foldconv_forward accepts FOLDCONV_FLAG_OUT_NCHW:
+                                       width-folded 16-bit plan on the streaming kernel, F a
+                                       multiple of 8, F*C_out a multiple of 64 and at most 1024,
+                                       W_out == F*W_out_fold, y below 4 GiB                     */
     int64_t gemm_M, gemm_N, gemm_K; /* implicit GEMM of the folded problem, dense K           */
     int64_t x_bytes, w_bytes, bias_bytes, w_exp_bytes, y_bytes, y_fold_bytes;
     int64_t workspace_bytes;        /* for foldconv_forward / foldconv_pack_filter            */
@@ -211,6 +219,10 @@ FOLDCONV_API int foldconv_unfold_output(foldconv_plan_t plan, const void *y_fold
  *     -> y [N][C_out][H_out][W_out] of the image, dropping folded slots at or
  *     beyond the output extent (Reconstruct step).
  * A plan made by foldconv_plan is taken as FOLDCONV_FOLD_W.
+ * Where shapes.out_nchw_fused is 1, foldconv_forward with
+ * FOLDCONV_FLAG_OUT_NCHW writes the same bytes as foldconv_forward with
+ * FOLDCONV_FLAG_KEEP_FOLDED followed by foldconv_unfold_output_nchw, without
+ * the intermediate tensor.
  */
 FOLDCONV_API int foldconv_expand_filter_oihw(foldconv_plan_t plan, const void *w_oihw, void *w_exp, void *stream);
 FOLDCONV_API int foldconv_fold_input_nchw(foldconv_plan_t plan, const void *x_nchw, void *x_fold, void *stream);
@@ -252,6 +264,8 @@ FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *
  * bias may be NULL.  workspace: shapes.workspace_bytes, 256-byte aligned,
  * may be NULL when that is 0; with FOLDCONV_FLAG_FILTER_COMPACT it is the
  * compact filter (shapes.filter_compact_bytes) and w_exp is ignored.
+ * With FOLDCONV_FLAG_OUT_NCHW the reconstructed output is written
+ * channels-first, y[n][co][h][F*w'+g] (shapes.y_bytes, 16-byte aligned).
  */
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,
@@ -266,8 +280,8 @@ FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, cons
  * from Channel Zero-Padding".  x and w are the ORIGINAL tensors; the padded
  * copies live in workspace (shapes.padded_workspace_bytes).  With
  * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again.
- * FOLDCONV_FLAG_KEEP_FOLDED, FOLDCONV_FLAG_DENSE_K and
- * FOLDCONV_FLAG_FILTER_COMPACT are ignored.
+ * FOLDCONV_FLAG_KEEP_FOLDED, FOLDCONV_FLAG_DENSE_K,
+ * FOLDCONV_FLAG_FILTER_COMPACT and FOLDCONV_FLAG_OUT_NCHW are ignored.
  */
 FOLDCONV_API int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias,
                         void *y, void *workspace, size_t workspace_bytes, unsigned flags,

@@ -6,6 +6,7 @@ library is loaded on first use; importing the package loads nothing.
 from .binding import (  # noqa: F401
     FLAG_DENSE_K,
     FLAG_FILTER_COMPACT,
+    FLAG_OUT_NCHW,
     FLAG_FILTER_PACKED,
     FLAG_KEEP_FOLDED,
     FLAG_RELU,

@@ -11,7 +11,7 @@ static int hip_status(int e) { return e == 0 ? FOLDCONV_OK : FOLDCONV_ERR_HIP; }
 
 static const unsigned kAllFlags =
     FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED |
-    FOLDCONV_FLAG_FILTER_COMPACT;
+    FOLDCONV_FLAG_FILTER_COMPACT | FOLDCONV_FLAG_OUT_NCHW;
 
 extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
     if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
@@ -106,12 +106,21 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
     g.out_row = (flags & FOLDCONV_FLAG_KEEP_FOLDED) ? g.Wf_out * g.NCo : s.W_out * s.C_out;
 
     int kernel = s.conv_kernel;
+    const bool out_nchw = (flags & FOLDCONV_FLAG_OUT_NCHW) != 0;
+    if (out_nchw) {
+        if (flags & FOLDCONV_FLAG_KEEP_FOLDED) return FOLDCONV_ERR_BADARG;
+        g.out_row = s.W_out;
+        int ks = 0;
+        if (!s.out_nchw_fused || !fc_stream_nchw_ok(g, g.band, &ks)) return FOLDCONV_ERR_UNSUPPORTED;
+    }
     if (compact) {
         // every kernel takes its filter operand from the workspace
         int st = check_ws(workspace, workspace_bytes, s.filter_compact_bytes);
         if (st) return st;
         if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
         g.compact = 1;
+        if (out_nchw)
+            return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, x_fold, workspace, bias, y, stream));
         return hip_status(
             fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, workspace, workspace, bias, y, stream));
     }
@@ -126,6 +135,8 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
             if (e) return FOLDCONV_ERR_HIP;
         }
     }
+    if (out_nchw)
+        return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, x_fold, workspace, bias, y, stream));
     return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, w_exp, workspace, bias, y, stream));
 }
 

@@ -1,0 +1,361 @@
+// Streaming MFMA convolution with a channels-first (NCHW) output, for width-folded
+// plans of small-K layers.
+//
+// The filter-stationary streaming kernel gives every wave 64 output columns
+// n = g*C_out + co, i.e. (part of) one output slot g.  In a channels-first
+// output y[n][co][h][F*w'+g] the slots of one folded pixel are neighbours along
+// w, so contiguous stores need all F slots of a run of pixels in one place.
+// Here one workgroup holds every column group of an M tile (F*C_out/64 waves, at
+// most 16): each wave computes its 32 pixels x 64 columns exactly as the
+// streaming kernel does (filter fragments resident in registers, band walk, bias
+// as a rank-1 MFMA), the workgroup assembles the 32 x F*C_out tile in LDS, and
+// all threads write it out channel by channel: a thread reads the same four
+// channels of eight neighbouring slots (eight 8-byte LDS reads), regroups the
+// 16-bit values in registers into four 16-byte pieces, one per channel, each
+// holding 8 consecutive image columns; a wave's store instruction covers a
+// contiguous run of 64 such pieces of one channel row.
+// paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
+// w = F w' + f, applied on the way to a channels-first tensor.
+#include <hip/hip_runtime.h>
+#include <type_traits>
+
+#include "launch.h"
+#include "mfma_types.h"
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename TR>
+__device__ __forceinline__ unsigned pack2n(float a, float b);
+template <>
+__device__ __forceinline__ unsigned pack2n<F16Traits>(float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v = {(_Float16)a, (_Float16)b};
+    return __builtin_bit_cast(unsigned, v);
+}
+template <>
+__device__ __forceinline__ unsigned pack2n<BF16Traits>(float a, float b) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    b2 v = {(__bf16)a, (__bf16)b};
+    return __builtin_bit_cast(unsigned, v);
+}
+
+constexpr unsigned kOutOfRangeN = 0xfffffff0u;  // beyond any resource extent used here (extents stay below 2^32 - 64)
+
+struct NchwArgs {
+    unsigned MT;          // 32-pixel M tiles
+    unsigned per_xcd;     // tiles per XCD partition (workgroup b runs on XCD b % 8)
+    unsigned wg_per_xcd;  // workgroups per partition = stride of a workgroup's tile walk
+    unsigned dW, dH, dI;  // that stride of 32*wg_per_xcd pixels as (folded column, row, image) steps
+    unsigned mgW, mgH;    // ceil(2^32 / Wf_out), ceil(2^32 / Hout)
+    unsigned x_bytes, y_bytes;
+    int ksteps;           // 16-wide K-steps per kh actually walked (<= KSM)
+    int pitch;            // bytes per pixel row of the assembled tile
+    int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
+};
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for_n(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for_n<I + 1, N>(f);
+    }
+}
+
+// floor(t / d) for t < d + 64 and d < 65000, with mg = ceil(2^32 / d)
+__device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigned d) {
+    return d == 1u ? t : __umulhi(t, mg);
+}
+
+// EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU>
+__global__ void __launch_bounds__(1024, 1)
+conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
+                        const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
+    using T = typename TR::T;
+    using Vec = typename TR::Vec;
+    constexpr int NT = 2, COLS = 64;
+    constexpr int kStores = 4;  // 16-byte stores per thread and tile, issued unconditionally
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];  // two tiles of 32 * pitch bytes
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int r = lane & 31, hf = lane >> 5;
+    const int n_lo = wave * COLS;
+    const int KH = EXACT ? KHM : g.KH, KS = EXACT ? KSM : a.ksteps;
+
+    int e_lo, e_hi;
+    fc_band_window(g, n_lo, n_lo + COLS, 8, &e_lo, &e_hi);
+    const int q_per_kh = g.kwin / 8;
+    const int e0 = e_lo + 8 * hf;  // this lane's extended channel at K-step 0
+
+    // ---- filter fragments, resident for the kernel's lifetime -----------------
+    Vec wf[KHM][KSM][NT];
+#pragma unroll
+    for (int kh = 0; kh < KHM; ++kh)
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int e = e0 + 16 * ks;
+                const int n = n_lo + 32 * nt + r;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (kh < KH && ks < KS && e < e_hi) {
+                    const int q = (e - g.e_min) >> 3;
+                    const long long ci = g.compact ? fc_compact_chunk(g, kh, q, n)
+                                                   : ((long long)kh * q_per_kh + q) * g.NCo + n;
+                    if (ci >= 0) v = wp[ci];  // off-band chunks of the compact form are zeros
+                }
+                wf[kh][ks][nt] = __builtin_bit_cast(Vec, v);
+            }
+    // bias enters as a rank-1 MFMA: A = bias in K slot 0, B = 1 in K slot 0
+    Vec bf[NT], ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = (T)0.0f;
+    if (hf == 0) ones[0] = (T)1.0f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bf[nt][i] = (T)0.0f;
+        const int n = n_lo + 32 * nt + r;
+        if (g.has_bias && hf == 0) bf[nt][0] = bias[n % g.Co];
+    }
+    unsigned ksmask = 0;  // K-steps whose chunk lies inside this wave's band window
+#pragma unroll
+    for (int ks = 0; ks < KSM; ++ks)
+        if (ks < KS && e0 + 16 * ks < e_hi) ksmask |= 1u << ks;
+
+    // Range-checked resources: a lane with nothing to read (zero padding, pixels past the end)
+    // or nothing to store uses an out-of-range offset; reads return zeros, stores are dropped.
+    // The input loads are issued from inline assembly and waited for with explicit counts (see
+    // the loop head): the compiler's own wait insertion would make every wave wait for its
+    // previous tile's stores before touching the next tile's input.
+    u32x4 xr;
+    {
+        const unsigned long long xa = (unsigned long long)x;
+        xr[0] = __builtin_amdgcn_readfirstlane((unsigned)xa);
+        xr[1] = __builtin_amdgcn_readfirstlane((unsigned)(xa >> 32) & 0xffffu);  // stride 0: raw buffer, byte offsets
+        xr[2] = __builtin_amdgcn_readfirstlane(a.x_bytes);
+        xr[3] = __builtin_amdgcn_readfirstlane(0x00020000u);
+    }
+    const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)a.y_bytes, 0x00020000);
+
+    // ---- this thread's share of the write-out: pixel sp of the tile, slots [8*sg8, 8*sg8+8),
+    //      channels [4*co4, 4*co4+4): 32 * (F/8) threads per channel quadruple, C_out/4 quadruples
+    const int g8n = g.F >> 3;
+    const int per_c4 = 32 * g8n;
+    const int co4 = t / per_c4;
+    const int sp = (t - co4 * per_c4) / g8n;
+    const int sg8 = (t - co4 * per_c4) - sp * g8n;
+    const int rd_off = sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;  // + k * C_out * 2 per slot
+    const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;             // bytes per channel plane
+
+    // tiles of this workgroup: its XCD's contiguous range, strided by the workgroups of that XCD
+    const unsigned xcd = blockIdx.x % 8u, wg = blockIdx.x / 8u;
+    const unsigned t_first = xcd * a.per_xcd;
+    const unsigned t_end = t_first + a.per_xcd < a.MT ? t_first + a.per_xcd : a.MT;
+
+    // first pixel of the workgroup's current tile, advanced incrementally
+    unsigned m0 = (t_first + wg) * 32u;
+    unsigned wo0 = m0 % (unsigned)g.Wf_out, ho0, img0;
+    {
+        const unsigned rowid = m0 / (unsigned)g.Wf_out;
+        ho0 = rowid % (unsigned)g.Hout;
+        img0 = rowid / (unsigned)g.Hout;
+    }
+    auto pixel = [&](unsigned wo_base, unsigned ho_base, unsigned img_base, unsigned i, unsigned &wo, unsigned &ho,
+                     unsigned &img) {
+        const unsigned tt = wo_base + i;
+        const unsigned q = small_div_n(tt, a.mgW, (unsigned)g.Wf_out);
+        wo = tt - q * (unsigned)g.Wf_out;
+        const unsigned hr = ho_base + q;
+        const unsigned q2 = small_div_n(hr, a.mgH, (unsigned)g.Hout);
+        ho = hr - q2 * (unsigned)g.Hout;
+        img = img_base + q2;
+    };
+    auto advance = [&]() {
+        m0 += a.wg_per_xcd * 32u;
+        wo0 += a.dW;
+        unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
+        wo0 -= c * (unsigned)g.Wf_out;
+        ho0 += a.dH + c;
+        c = ho0 >= (unsigned)g.Hout ? 1u : 0u;
+        ho0 -= c * (unsigned)g.Hout;
+        img0 += a.dI + c;
+    };
+
+    u32x4 xf[KHM][KSM];
+    auto load_tile = [&]() {
+        unsigned wo, ho, img;
+        pixel(wo0, ho0, img0, (unsigned)r, wo, ho, img);
+        const bool vm = m0 + (unsigned)r < (unsigned)g.M;
+        const int col0 = (int)wo * g.FC + e0;  // column of K-step 0 inside the input row
+        const int pix0 = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col0;
+#pragma unroll
+        for (int kh = 0; kh < KHM; ++kh) {
+            const int hi = (int)ho + kh - g.pad_h;
+            const bool rv = vm && kh < KH && hi >= 0 && hi < g.H;
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks) {
+                // in range: row hi exists and the 8-element chunk [col, col+8) lies inside it
+                const int col = col0 + 16 * ks;
+                const bool ok = rv && ((ksmask >> ks) & 1u) && col >= 0 && col < g.in_row;
+                const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRangeN;
+                asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(xf[kh][ks]) : "v"(voff), "s"(xr) : "memory");
+            }
+        }
+    };
+
+    // Nothing the compiler tracks may be in flight when the hand-counted loads start.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    load_tile();
+    // Drain the first tile's loads here: the loop head then only ever waits for loads that were
+    // issued ahead of the four stores of the previous tile, and leaves those stores in flight.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int buf = 0;
+    for (unsigned mt = t_first + wg; mt < t_end; mt += a.wg_per_xcd) {
+        floatx16_t acc[NT];
+        floatx16_t zero;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
+        static_for_n<0, KHM * KSM>([&](auto step) {
+            constexpr int idx = decltype(step)::value;
+            constexpr int kh = idx / KSM, ks = idx % KSM;
+            if (EXACT || (kh < KH && ks < KS)) {
+                // Vector-memory operations retire in issue order.  Behind this fragment's load the
+                // wave has issued the remaining fragment loads of the tile and then exactly
+                // kStores stores, so the fragment has landed once at most that many operations
+                // are outstanding.  Instances with run-time K guards take the full wait instead.
+                constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) + kStores : 0;
+                asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");
+                const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
+            }
+        });
+        const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_ho0 = ho0, cur_img0 = img0;
+        advance();
+        // The next tile's input stays in flight across the write-out.  After the last tile this
+        // fetches a tile that is never used; every lane's address is either inside x or out of
+        // the resource's range, so the load is always safe.
+        load_tile();
+
+        // ---- assemble the tile in LDS: pixel rows of F*C_out columns ----
+        unsigned char *tb = tile_lds + buf * (32 * a.pitch);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32x2 pk = {pack2n<TR>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2n<TR>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
+                if (RELU) {
+                    // max(v, 0) on the rounded 16-bit patterns as signed integers
+                    typedef short s16x4 __attribute__((ext_vector_type(4)));
+                    const s16x4 z = {0, 0, 0, 0};
+                    pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
+                }
+                const int n = n_lo + 32 * nt + 8 * q + 4 * hf;
+                const int slot8 = (n / g.Co) >> 3;
+                *reinterpret_cast<u32x2 *>(tb + r * a.pitch + n * 2 + slot8 * a.skew) = pk;
+            }
+        // One barrier per tile is enough with two buffers: this buffer is written again two tiles
+        // on, and no wave gets there before every wave has passed the next tile's barrier, which
+        // each does only after finishing its reads below.
+        __syncthreads();
+
+        // ---- write out: y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8) for i = 0..3 ----
+        {
+            unsigned wo, ho, img;
+            pixel(cur_wo0, cur_ho0, cur_img0, (unsigned)sp, wo, ho, img);
+            const bool ok = cur_m0 + (unsigned)sp < (unsigned)g.M;
+            const unsigned off0 =
+                2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
+                      wo * (unsigned)g.F + 8u * (unsigned)sg8);
+            u32x2 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const u32x2 *>(tb + rd_off + k * g.Co * 2);
+#pragma unroll
+            for (int i = 0; i < kStores; ++i) {
+                u32x4 out;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const unsigned lo = v[2 * j][i >> 1], hi = v[2 * j + 1][i >> 1];
+                    out[j] = (i & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(out, yr, ok ? off0 + (unsigned)i * plane_b : kOutOfRangeN, 0, 2 /* nt */);
+            }
+        }
+        buf ^= 1;
+    }
+}
+
+static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
+
+template <typename TR, int KHM, int KSM>
+int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
+    using T = typename TR::T;
+    NchwArgs a;
+    const int g8n = g.F / 8;
+    a.skew = g8n > 1 ? 256 / g8n : 0;
+    if (a.skew % 8 != 0) a.skew = 8;
+    a.pitch = g.NCo * 2 + g8n * a.skew + 8;
+    const unsigned lds_bytes = 2u * 32u * (unsigned)a.pitch;
+    const unsigned threads = (unsigned)g.NCo;  // one wave per 64 columns
+    // workgroups resident per compute unit: 16 waves at the register budget of the launch bounds, 160 KB of LDS
+    unsigned per_cu = 1024u / threads;
+    if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
+    if (per_cu < 1) per_cu = 1;
+    a.MT = (unsigned)((g.M + 31) / 32);
+    a.per_xcd = (a.MT + 7) / 8;
+    a.wg_per_xcd = 32u * per_cu;
+    if (a.wg_per_xcd > a.per_xcd) a.wg_per_xcd = a.per_xcd;
+    const long long S = 32LL * a.wg_per_xcd, plane = (long long)g.Hout * g.Wf_out;
+    a.dI = (unsigned)(S / plane);
+    a.dH = (unsigned)((S % plane) / g.Wf_out);
+    a.dW = (unsigned)((S % plane) % g.Wf_out);
+    a.mgW = magic_for((unsigned)g.Wf_out);
+    a.mgH = magic_for((unsigned)g.Hout);
+    a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
+    a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
+    a.ksteps = ksteps;
+    const unsigned blocks = a.wg_per_xcd * 8;
+    auto go = [&](auto kernel) {
+        // more than 64 KB of dynamic LDS has to be allowed per kernel, once
+        static bool allowed = false;  // benign race: every thread sets the same attribute
+        if (!allowed) {
+            if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 163840) != hipSuccess)
+                return (int)hipGetLastError();
+            allowed = true;
+        }
+        kernel<<<blocks, threads, lds_bytes, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
+        return (int)hipGetLastError();
+    };
+    const bool exact = g.KH == KHM && ksteps == KSM;
+    if (exact && g.relu) return go(conv_stream_nchw_kernel<TR, KHM, KSM, true, true>);
+    if (exact) return go(conv_stream_nchw_kernel<TR, KHM, KSM, true, false>);
+    if (g.relu) return go(conv_stream_nchw_kernel<TR, KHM, KSM, false, true>);
+    return go(conv_stream_nchw_kernel<TR, KHM, KSM, false, false>);
+}
+
+template <typename TR>
+int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
+    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1>(g, ksteps, x, wp, bias, y, st);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
+                               void *y, void *stream) {
+    int ksteps = 0;
+    if (!fc_stream_nchw_ok(g, g.band, &ksteps)) return (int)hipErrorInvalidValue;
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == FOLDCONV_F16) return launch_any<F16Traits>(g, ksteps, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16) return launch_any<BF16Traits>(g, ksteps, x, w_pack, bias, y, st);
+    return (int)hipErrorInvalidValue;
+}

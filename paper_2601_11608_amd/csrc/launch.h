@@ -42,6 +42,11 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
                           void *y, void *stream);
 int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
                          void *y, void *stream);
+// Streaming kernel that writes a channels-first output (g.out_row = W_out of the image); false if the
+// geometry does not fit it.
+bool fc_stream_nchw_ok(const ConvGeom &g, int band, int *ksteps);
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,
+                               const void *bias, void *y, void *stream);
 bool fc_tiled_ok(const ConvGeom &g);
 int fc_tiled_bn(const ConvGeom &g);  // output columns per workgroup tile of the tiled kernel: 128 or 256
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,

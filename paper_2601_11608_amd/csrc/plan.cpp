@@ -118,6 +118,12 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
     s.padded_kernel = fc_choose_kernel(q, dtype);
+    {
+        ConvGeom gn = g;  // the streaming kernel's channels-first variant sees W_out as the stored row
+        gn.out_row = (int)W_out;
+        int ks = 0;
+        s.out_nchw_fused = (s.conv_kernel == FC_KERNEL_STREAM && fc_stream_nchw_ok(gn, 1, &ks)) ? 1 : 0;
+    }
 
     const long long xpad_bytes = (long long)N * H * W * C_pad * eb;
     const long long wpad_bytes = (long long)KH * KW * C_pad * Co_pad * eb;
@@ -157,6 +163,8 @@ extern "C" int foldconv_plan_nchw(int N, int C_in, int H, int W, int C_out, int 
     if (st != FOLDCONV_OK) return st;
     (*out)->fold_axis = fold_axis;
     (*out)->s.fold_axis = fold_axis;
+    // slots of a height fold are neighbours along h, not along the contiguous axis of y
+    if (fold_axis == FOLDCONV_FOLD_H) (*out)->s.out_nchw_fused = 0;
     return FOLDCONV_OK;
 }
 

@@ -1,0 +1,153 @@
+"""GPU parity of the folded convolution that writes its output channels-first in
+the same launch (FLAG_OUT_NCHW), through the C ABI: bit-identical to the
+two-step route (folded output, then the channels-first reconstruct) and within
+the relative-L2 tolerance of the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, TORCH_DT, f64, rel_l2_per_image
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fc():
+    import paper_2601_11608_amd as fc
+
+    fc.load_library()
+    assert torch.cuda.is_available()
+    return fc
+
+
+def draw(shape, dt, seed):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    return torch.randn(shape, generator=g).to(TORCH_DT[dt])
+
+
+def prepare(fc, plan, x, w):
+    s = plan.shapes
+    dt = x.dtype
+    w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=dt, device="cuda")
+    fc.foldconv_expand_filter_oihw(plan, w.cuda(), w_exp)
+    xf = torch.empty(x.numel(), dtype=dt, device="cuda")
+    fc.foldconv_fold_input_nchw(plan, x.cuda(), xf)
+    ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+    return xf, w_exp, ws
+
+
+def two_step(fc, plan, xf, w_exp, b, ws, flags):
+    s = plan.shapes
+    yf = torch.full((s.y_fold_bytes // s.elem_bytes,), float("nan"), dtype=xf.dtype, device="cuda")
+    fc.foldconv_forward(plan, xf, w_exp, b, yf, ws, fc.FLAG_KEEP_FOLDED | flags)
+    y = torch.full((s.y_bytes // s.elem_bytes,), float("nan"), dtype=xf.dtype, device="cuda")
+    fc.foldconv_unfold_output_nchw(plan, yf, y)
+    return y
+
+
+def fused(fc, plan, xf, w_exp, b, ws, flags):
+    s = plan.shapes
+    y = torch.full((s.y_bytes // s.elem_bytes,), float("nan"), dtype=xf.dtype, device="cuda")
+    fc.foldconv_forward(plan, xf, w_exp, b, y, ws, fc.FLAG_OUT_NCHW | flags)
+    return y
+
+
+# N, C, H, W, Co, KH, KW, pad, F, bias, relu
+FUSED = [
+    (2, 3, 32, 48, 64, 3, 3, 1, 16, True, True),      # headline structure: 16 waves per workgroup
+    (3, 3, 5, 48, 64, 3, 3, 1, 16, True, False),      # 45 folded pixels: one full tile and a ragged one
+    (1, 1, 24, 64, 32, 3, 3, 1, 8, False, True),      # 4 waves, several workgroups per compute unit
+    (3, 1, 17, 96, 16, 3, 3, 1, 32, True, False),     # F = 32, C_out = 16
+    (2, 2, 9, 40, 16, 1, 1, 0, 8, True, True),        # 1 x 1 kernel
+    (1, 1, 12, 128, 12, 3, 3, 1, 16, True, False),    # C_out = 12: 64-column waves straddle slots
+    (16, 3, 128, 128, 64, 3, 3, 1, 16, True, True),   # 512 tiles: every workgroup walks two
+    (2, 2, 10, 64, 24, 2, 3, 1, 8, False, False),     # KH = 2: the guarded instance
+]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("case", FUSED, ids=lambda c: "x".join(map(str, c[:9])))
+def test_fused_nchw_output(fc, oracle, case, dt):
+    N, C, H, W, Co, KH, KW, pad, F, hb, relu = case
+    x = draw((N, C, H, W), dt, 41)
+    w = (draw((Co, C, KH, KW), dt, 42) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+    b = draw((Co,), dt, 43).cuda() if hb else None
+    plan = fc.foldconv_plan_nchw(N, C, H, W, Co, KH, KW, pad, F, fc.FOLD_W, x.dtype)
+    s = plan.shapes
+    assert s.out_nchw_fused == 1, s.as_dict()
+    print("fused nchw", case, dt, flush=True)
+    xf, w_exp, ws = prepare(fc, plan, x, w)
+    flags = fc.FLAG_RELU if relu else 0
+    want = two_step(fc, plan, xf, w_exp, b, ws, flags)
+    got = fused(fc, plan, xf, w_exp, b, ws, flags)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(got).any()), "unwritten output elements"
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    # the compact filter gives the same bytes
+    cws = torch.empty(int(s.filter_compact_bytes), dtype=torch.uint8, device="cuda")
+    fc.foldconv_pack_filter_compact(plan, w.permute(2, 3, 1, 0).contiguous().cuda(), cws)
+    got_c = fused(fc, plan, xf, None, b, cws, flags | fc.FLAG_FILTER_COMPACT)
+    torch.cuda.synchronize()
+    assert torch.equal(got_c.view(torch.int16), want.view(torch.int16))
+    if N * Co * H * W <= 1 << 21:
+        ph, pw = oracle.axis_pads(KH, KW, pad)
+        ref = oracle.conv_direct_nchw(f64(x), f64(w), None if b is None else f64(b.cpu()), ph, pw, relu)
+        assert rel_l2_per_image(f64(got.cpu()).reshape(ref.shape), ref) <= TOL[dt]
+
+
+def test_fused_nchw_headline_layer_full_size(fc, oracle):
+    """The headline layer (N=64, 3x224x224 -> 64 channels, fp16, F=16) written channels-first in one
+    launch: identical to the two-step route everywhere, sampled images against the oracle."""
+    from paper_2601_11608_amd import workloads as wl
+
+    layers, x, wts, bs = wl.make_config("c2")
+    l = layers[0]
+    xn = x.permute(0, 3, 1, 2).contiguous()
+    wn = wts[0].permute(3, 2, 0, 1).contiguous()
+    plan = fc.foldconv_plan_nchw(l.N, l.C_in, l.H, l.W, l.C_out, l.KH, l.KW, l.pad, l.F, fc.FOLD_W, xn.dtype)
+    assert plan.shapes.out_nchw_fused == 1
+    print("fused nchw full size", flush=True)
+    xf, w_exp, ws = prepare(fc, plan, xn, wn)
+    b = bs[0].cuda()
+    want = two_step(fc, plan, xf, w_exp, b, ws, 0)
+    got = fused(fc, plan, xf, w_exp, b, ws, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    y = got.cpu().reshape(l.N, l.C_out, l.H, l.W)
+    images = [0, 29, 63]
+    ref = oracle.conv_direct_nchw(f64(xn[images]), f64(wn), f64(bs[0]), 1, 1)
+    assert rel_l2_per_image(f64(y[images]), ref) <= TOL["f16"]
+
+
+def test_fused_nchw_refusals(fc):
+    dt = torch.float16
+    # geometries the fused kernel does not serve report it in the plan and are refused by the call
+    for args, axis in [((1, 3, 8, 16, 4, 3, 3, 1, 16), fc.FOLD_W),      # one wave would span all 16 slots: K too wide
+                       ((1, 12, 16, 32, 16, 3, 3, 1, 8), fc.FOLD_W),    # C_in = 12: five K-steps per kh
+                       ((1, 3, 16, 30, 64, 3, 3, 0, 2), fc.FOLD_W),     # F not a multiple of 8
+                       ((1, 3, 16, 32, 64, 3, 3, 0, 16), fc.FOLD_W),    # VALID: W_out = 30 is not F * W'_out
+                       ((2, 3, 32, 48, 64, 3, 3, 1, 16), fc.FOLD_H)]:   # height fold
+        plan = fc.foldconv_plan_nchw(*args, axis, dt)
+        s = plan.shapes
+        assert s.out_nchw_fused == 0, args
+        x = torch.zeros(s.x_bytes // 2, dtype=dt, device="cuda")
+        w = torch.zeros(s.w_exp_bytes // 2, dtype=dt, device="cuda")
+        y = torch.zeros(max(s.y_bytes, s.y_fold_bytes) // 2, dtype=dt, device="cuda")
+        ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device="cuda")
+        with pytest.raises(fc.FoldconvError) as e:
+            fc.foldconv_forward(plan, x, w, None, y, ws, fc.FLAG_OUT_NCHW)
+        assert e.value.status == -3
+    plan = fc.foldconv_plan_nchw(2, 3, 32, 48, 64, 3, 3, 1, 16, fc.FOLD_W, dt)
+    s = plan.shapes
+    x = torch.zeros(s.x_bytes // 2, dtype=dt, device="cuda")
+    w = torch.zeros(s.w_exp_bytes // 2, dtype=dt, device="cuda")
+    y = torch.zeros(s.y_bytes // 2, dtype=dt, device="cuda")
+    ws = torch.empty(int(s.workspace_bytes), dtype=torch.uint8, device="cuda")
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_forward(plan, x, w, None, y, ws, fc.FLAG_OUT_NCHW | fc.FLAG_KEEP_FOLDED)
+    assert e.value.status == -1
+    # the dense walk needs more K-steps per kh than the fused kernel holds
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_forward(plan, x, w, None, y, ws, fc.FLAG_OUT_NCHW | fc.FLAG_DENSE_K)
+    assert e.value.status == -3
