@@ -257,6 +257,14 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
+        if (!EXACT) {
+            // Instances with run-time K guards drain every fragment load here, ahead of the guards:
+            // a fragment whose K-step is guarded off is never waited for below, and its registers
+            // must not be handed to anything else while its load is still in flight.
+#pragma unroll
+            for (int i = 0; i < KHM * KSM; ++i)
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(xf[i / KSM][i % KSM]) : : "memory");
+        }
         static_for<0, KHM * KSM>([&](auto step) {
             constexpr int idx = decltype(step)::value;
             constexpr int kh = idx / KSM, ks = idx % KSM;
@@ -265,7 +273,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 // the wave has issued the remaining fragment loads of the tile and then exactly
                 // PASSES stores, so the fragment has landed once at most that many operations
                 // are outstanding.  (Guarded-off K-steps only make the count stricter.)
-                // Instances with run-time K guards take the plain full wait instead.
+                // Instances with run-time K guards have drained everything above.
                 constexpr int kBehindAll = EXACT ? (KHM * KSM - 1 - idx) + PASSES : 0;
                 constexpr int kBehind = kBehindAll < 63 ? kBehindAll : 63;
                 asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");

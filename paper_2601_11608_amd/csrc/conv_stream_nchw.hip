@@ -223,6 +223,14 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
+        if (!EXACT) {
+            // Instances with run-time K guards drain every fragment load here, ahead of the guards:
+            // a fragment whose K-step is guarded off is never waited for below, and its registers
+            // must not be handed to anything else while its load is still in flight.
+#pragma unroll
+            for (int i = 0; i < KHM * KSM; ++i)
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(xf[i / KSM][i % KSM]) : : "memory");
+        }
         static_for_n<0, KHM * KSM>([&](auto step) {
             constexpr int idx = decltype(step)::value;
             constexpr int kh = idx / KSM, ks = idx % KSM;
@@ -230,7 +238,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 // Vector-memory operations retire in issue order.  Behind this fragment's load the
                 // wave has issued the remaining fragment loads of the tile and then exactly
                 // kStores stores, so the fragment has landed once at most that many operations
-                // are outstanding.  Instances with run-time K guards take the full wait instead.
+                // are outstanding.  Instances with run-time K guards have drained everything above.
                 constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) + kStores : 0;
                 asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");
                 const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);

@@ -113,6 +113,24 @@ def test_headline_layer_numbers(fc):
     assert abs(s.issued_flops_dense - 177.57e9) < 1e8
 
 
+def test_fused_channels_first_output_is_reported_in_the_plan(fc):
+    """shapes.out_nchw_fused: width-folded 16-bit plans whose slots tile whole 16-byte pieces of y."""
+    import torch
+
+    def fused(*a, axis=None, dt=torch.float16):
+        return fc.foldconv_plan_nchw(*a, fc.FOLD_W if axis is None else axis, dt).shapes.out_nchw_fused
+
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16) == 1                      # the headline layer
+    assert fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes.out_nchw_fused == 1
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.bfloat16) == 1
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.float32) == 0    # fp32 runs the gather kernel
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 0      # slots are neighbours along h
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 4) == 0                       # F not a multiple of 8
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 32) == 0                      # F*C_out = 2048 > 1024
+    assert fused(64, 3, 224, 224, 64, 3, 3, 0, 16) == 0                      # W_out = 222 is not F*W'_out
+    assert fused(8, 132, 112, 112, 64, 3, 3, 1, 8) == 0                      # large K: the tiled kernel
+
+
 def test_plan_errors(fc):
     with pytest.raises(fc.FoldconvError) as e:
         fc.foldconv_plan(1, 8, 10, 3, 4, 3, 3, 1, 4, "float16")

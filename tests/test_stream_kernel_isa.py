@@ -94,3 +94,129 @@ def test_hand_counted_waits_cover_every_fragment(asm):
             assert not (vregs(l) & pending), "%s: '%s' touches registers of a load in flight" % (name, l)
         checked += 1
     assert checked >= 20
+
+
+# ---- the same property by walking every path through the control flow -------------------------
+# Used for the channels-first streaming kernel, whose loop the compiler rotates (the previous tile's
+# stores sit at the top of the loop text), and as a second check of the channels-last one.
+NCHW_SRC = os.path.join(ROOT, "paper_2601_11608_amd", "csrc", "conv_stream_nchw.hip")
+
+
+def compile_to_asm(src):
+    if not os.path.exists(HIPCC):
+        pytest.skip("hipcc not available")
+    with tempfile.TemporaryDirectory() as d:
+        out = os.path.join(d, "k.s")
+        subprocess.check_call(
+            [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+             "-packed-fp32-ops", "-S", "--cuda-device-only", src, "-o", out],
+            stderr=subprocess.DEVNULL)
+        return open(out).read()
+
+
+def instructions(asm, name):
+    i = asm.index(name + ":")
+    body = asm[i:asm.index(".Lfunc_end", i)]       # a kernel may have several s_endpgm
+    out = []
+    for l in body.splitlines()[1:]:
+        l = l.split(";")[0].strip()
+        if l and (not l.startswith(".") or re.match(r"\.LBB\d+_\d+:", l)):
+            out.append(l)
+    return out
+
+
+def walk_paths(lines, name):
+    """Loads complete in issue order and a wait with count N leaves at most N vector-memory
+    operations outstanding, so a hand-issued load has landed once a wait's count is no larger than
+    the number of vector-memory operations issued after it.  State per path: the hand-issued loads
+    in flight, each with its destination registers and that number.  Fails if anything touches the
+    registers of a load that has not landed."""
+    label_at = {l[:-1]: i for i, l in enumerate(lines) if l.endswith(":")}
+    seen, work, ends, landed_by_count = set(), [(0, ())], 0, 0
+    while work:
+        pc, state = work.pop()
+        while True:
+            l = lines[pc]
+            if l.endswith(":"):
+                if (pc, state) in seen:
+                    break
+                seen.add((pc, state))
+                assert len(seen) < 200000, name
+                pc += 1
+                continue
+            if l == "s_endpgm":
+                ends += 1
+                break
+            b = re.match(r"s_(c?)branch\w* (\.LBB\d+_\d+)$", l)
+            if b:
+                target = label_at[b.group(2)]
+                if b.group(1):
+                    work.append((target, state))
+                    pc += 1
+                else:
+                    pc = target
+                continue
+            w = re.search(r"s_waitcnt.*vmcnt\((\d+)\)", l)
+            if w:
+                n = int(w.group(1))
+                if n > 0:
+                    landed_by_count += sum(1 for regs, after in state if after >= n)
+                state = tuple((regs, after) for regs, after in state if after < n)
+                pc += 1
+                continue
+            touched = vregs(l)
+            m = re.match(r"buffer_load_dwordx4 v\[(\d+):(\d+)\]", l)
+            for regs, _ in state:
+                assert not (touched & regs), "%s: '%s' touches registers of a load in flight" % (name, l)
+            if re.match(r"(buffer|global|flat|scratch)_(load|store|atomic)", l):
+                state = tuple((regs, min(after + 1, 64)) for regs, after in state)
+            if m:
+                state = state + ((frozenset(range(int(m.group(1)), int(m.group(2)) + 1)), 0),)
+            pc += 1
+    assert ends >= 1
+    return landed_by_count
+
+
+@pytest.fixture(scope="module")
+def nchw_asm():
+    return compile_to_asm(NCHW_SRC)
+
+
+def test_channels_first_kernel_waits(nchw_asm):
+    names = sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_123conv_stream_nchw_kernelI\S+?):", nchw_asm, re.M)))
+    assert len(names) == 16
+    for name in names:
+        exact = re.search(r"TraitsLi\d+ELi\d+ELb([01])ELb[01]E", name).group(1) == "1"
+        lines = instructions(nchw_asm, name)
+        partial = walk_paths(lines, name)
+        counts = [int(w) for l in lines for w in re.findall(r"s_waitcnt.*vmcnt\((\d+)\)", l)]
+        if exact:
+            # the stores of the previous tile stay in flight: some waits leave 4 or more outstanding
+            assert partial > 0 and max(counts) >= 4, name
+        else:
+            assert partial == 0, name
+
+
+def test_channels_last_kernel_waits_by_path_walk(asm):
+    names = sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_118conv_stream_kernelI\S+?):", asm, re.M)))
+    for name in names:
+        walk_paths(instructions(asm, name), name)
+
+
+@pytest.mark.parametrize("mutation", ["weak_wait", "drop_store"])
+def test_path_walk_catches_planted_mistakes(nchw_asm, mutation):
+    name = next(n for n in sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_123conv_stream_nchw_kernelI\S+?):", nchw_asm, re.M)))
+                if "Li3ELi1ELb1ELb0E" in n)
+    lines = instructions(nchw_asm, name)
+    walk_paths(lines, name)
+    bad = list(lines)
+    if mutation == "weak_wait":
+        # one more operation allowed in flight than there are behind the fragment's load
+        i = max(i for i, l in enumerate(bad) if re.match(r"s_waitcnt vmcnt\(4\)$", l))
+        bad[i] = "s_waitcnt vmcnt(5)"
+    else:
+        # one store fewer between the loads and the wait: the count no longer covers the load
+        i = max(i for i, l in enumerate(bad) if l.startswith("buffer_store_dwordx4"))
+        bad[i] = "s_nop 0"
+    with pytest.raises(AssertionError):
+        walk_paths(bad, name)
