@@ -77,3 +77,46 @@ class FoldedStack:
                 l.forward(a, y, flags, compact=compact)
             a = y
         return a
+
+
+class ChannelsFirstLayer:
+    """One convolution layer on channels-first tensors: x [N][C_in][H][W], w [C_out][C_in][KH][KW],
+    y [N][C_out][H_out][W_out].  The fold is a re-indexing kernel here; the convolution writes y
+    channels-first itself where the plan allows it (shapes.out_nchw_fused), otherwise it writes the
+    folded output and the reconstruct kernel re-indexes that."""
+
+    def __init__(self, layer, w_oihw, b, fold_axis=fc.FOLD_W, device="cuda"):
+        self.layer = layer
+        self.dtype = w_oihw.dtype
+        self.plan = fc.foldconv_plan_nchw(layer.N, layer.C_in, layer.H, layer.W, layer.C_out, layer.KH, layer.KW,
+                                          layer.pad, layer.F, fold_axis, w_oihw.dtype)
+        s = self.plan.shapes
+        self.fused = bool(s.out_nchw_fused)
+        self.w = w_oihw.to(device).contiguous()
+        self.b = None if b is None else b.to(device).contiguous()
+        self.w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=self.dtype, device=device)
+        fc.foldconv_expand_filter_oihw(self.plan, self.w, self.w_exp)
+        self.ws = torch.empty(max(int(s.workspace_bytes), 256), dtype=torch.uint8, device=device)
+        fc.foldconv_pack_filter(self.plan, self.w_exp, self.ws)
+        self.x_fold = torch.empty(s.x_bytes // s.elem_bytes, dtype=self.dtype, device=device)
+        self.y_fold = None if self.fused else torch.empty(s.y_fold_bytes // s.elem_bytes, dtype=self.dtype, device=device)
+
+    def out_shape(self):
+        s = self.plan.shapes
+        if s.fold_axis == fc.FOLD_H:  # the plan describes the transposed image
+            return (s.N, s.C_out, s.W_out, s.H_out)
+        return (s.N, s.C_out, s.H_out, s.W_out)
+
+    def new_output(self):
+        return torch.empty(self.out_shape(), dtype=self.dtype, device=self.w.device)
+
+    def forward(self, x, y):
+        flags = fc.FLAG_FILTER_PACKED | (fc.FLAG_RELU if self.layer.relu else 0)
+        fc.foldconv_fold_input_nchw(self.plan, x, self.x_fold)
+        if self.fused:
+            fc.foldconv_forward(self.plan, self.x_fold, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW)
+        else:
+            fc.foldconv_forward(self.plan, self.x_fold, self.w_exp, self.b, self.y_fold, self.ws,
+                                flags | fc.FLAG_KEEP_FOLDED)
+            fc.foldconv_unfold_output_nchw(self.plan, self.y_fold, y)
+        return y

@@ -63,6 +63,9 @@ FUSED = [
     (1, 1, 12, 128, 12, 3, 3, 1, 16, True, False),    # C_out = 12: 64-column waves straddle slots
     (16, 3, 128, 128, 64, 3, 3, 1, 16, True, True),   # 512 tiles: every workgroup walks two
     (2, 2, 10, 64, 24, 2, 3, 1, 8, False, False),     # KH = 2: the guarded instance
+    (70, 1, 1, 16, 8, 1, 1, 0, 16, True, False),      # one folded pixel per image: a tile spans 32 images
+    (5, 1, 3, 32, 16, 3, 3, 1, 16, True, True),       # two folded pixels per row, three rows
+    (1, 1, 300, 8, 64, 3, 1, 1, 8, False, False),     # one folded pixel per row, 3 x 1 kernel
 ]
 
 
@@ -118,6 +121,26 @@ def test_fused_nchw_headline_layer_full_size(fc, oracle):
     images = [0, 29, 63]
     ref = oracle.conv_direct_nchw(f64(xn[images]), f64(wn), f64(bs[0]), 1, 1)
     assert rel_l2_per_image(f64(y[images]), ref) <= TOL["f16"]
+
+
+@pytest.mark.parametrize("axis", ["W", "H"])
+def test_channels_first_layer_runner(fc, oracle, axis):
+    """runner.ChannelsFirstLayer takes the fused route for a width fold and the two-step route for a
+    height fold; both match the oracle."""
+    from paper_2601_11608_amd import workloads as wl
+    from paper_2601_11608_amd.runner import ChannelsFirstLayer
+
+    l = wl.Layer("t", 2, 32, 48, 3, 64, 3, 3, 1, 16, "f16", True, "normal", relu=True)
+    x = draw((l.N, l.C_in, l.H, l.W), "f16", 51)
+    w = (draw((l.C_out, l.C_in, 3, 3), "f16", 52) * (1.0 / np.sqrt(27))).to(torch.float16)
+    b = draw((l.C_out,), "f16", 53)
+    L = ChannelsFirstLayer(l, w, b, fc.FOLD_W if axis == "W" else fc.FOLD_H)
+    assert L.fused == (axis == "W")
+    y = L.forward(x.cuda(), L.new_output())
+    torch.cuda.synchronize()
+    ref = oracle.conv_direct_nchw(f64(x), f64(w), f64(b), 1, 1, True)
+    assert tuple(y.shape) == ref.shape
+    assert rel_l2_per_image(f64(y.cpu()), ref) <= TOL["f16"]
 
 
 def test_fused_nchw_refusals(fc):
