@@ -8,6 +8,9 @@ int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const voi
             // The dense walk may need more K-steps than any streaming instance holds;
             // the tiled kernel reads the same packed filter.
             StreamShape sh;
+            // Dense walk with the whole K extent in registers: the variant that shares each input
+            // tile among four waves through LDS.
+            if (!g.band && fc_stream_lds_ok(g)) return fc_launch_conv_stream_lds(dt, g, x, w_pack, bias, y, stream);
             if (fc_stream_shape(g, g.band, &sh)) return fc_launch_conv_stream(dt, g, x, w_pack, bias, y, stream);
             return fc_launch_conv_tiled(dt, g, x, w_pack, bias, y, stream);
         }

@@ -47,6 +47,10 @@ int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, 
 bool fc_stream_nchw_ok(const ConvGeom &g, int band, int *ksteps);
 int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,
                                const void *bias, void *y, void *stream);
+// Streaming kernel with the input tile staged through LDS (dense walks whose K extent fits the registers).
+bool fc_stream_lds_ok(const ConvGeom &g);
+int fc_launch_conv_stream_lds(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,
+                              const void *bias, void *y, void *stream);
 bool fc_tiled_ok(const ConvGeom &g);
 int fc_tiled_bn(const ConvGeom &g);  // output columns per workgroup tile of the tiled kernel: 128 or 256
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,

@@ -68,6 +68,19 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     return false;
 }
 
+bool fc_stream_lds_ok(const ConvGeom &g) {
+    if (!vector_ok(g)) return false;
+    if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
+    if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
+    if (g.M >= (1LL << 31) - (1LL << 20)) return false;
+    // four waves of 64 columns per workgroup; compiled instance: KH = 3 and 18 chunks of 8 K values per kh
+    // (F*C_in = 48 with KW' = 3: the first-layer shapes)
+    if (g.NCo % 256 != 0 || g.NCo / 256 > 32) return false;
+    // stored rows are whole folded rows (kept folded, or the reconstruct is an alias)
+    if (g.out_row != g.Wf_out * g.NCo) return false;
+    return g.KH == 3 && g.kwin == 18 * 8;
+}
+
 bool fc_stream_nchw_ok(const ConvGeom &g, int band, int *ksteps) {
     // g.out_row is the image's W_out here (elements per channel row of y).
     // Whole 16-byte pieces of 8 slots, one wave per 64 columns, at most 16 waves, 4 channels per LDS read.

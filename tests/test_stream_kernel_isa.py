@@ -220,3 +220,106 @@ def test_path_walk_catches_planted_mistakes(nchw_asm, mutation):
         bad[i] = "s_nop 0"
     with pytest.raises(AssertionError):
         walk_paths(bad, name)
+
+
+# ---- the LDS-staged dense-walk kernel: loads that deposit into LDS, counted by hand -------------
+LDS_SRC = os.path.join(ROOT, "paper_2601_11608_amd", "csrc", "conv_stream_lds.hip")
+
+
+def walk_lds_loads(lines, name, per_tile):
+    """Every path through the kernel.  State: for each load-to-LDS in flight, the number of
+    vector-memory operations issued after it (loads complete in issue order; a wait with count N
+    leaves at most N operations outstanding).  Checks that every such load sets M0 in the
+    instruction before it, that at every barrier only the loads of one tile (the one after the
+    tile being published) can still be in flight, and that none is in flight at the end."""
+    label_at = {l[:-1]: i for i, l in enumerate(lines) if l.endswith(":")}
+    seen, work, ends, barriers = set(), [(0, ())], 0, 0
+    while work:
+        pc, state = work.pop()
+        while True:
+            l = lines[pc]
+            if l.endswith(":"):
+                if (pc, state) in seen:
+                    break
+                seen.add((pc, state))
+                assert len(seen) < 200000, name
+                pc += 1
+                continue
+            if l == "s_endpgm":
+                assert not state, "%s: loads-to-LDS in flight at the end of the kernel" % name
+                ends += 1
+                break
+            b = re.match(r"s_(c?)branch\w* (\.LBB\d+_\d+)$", l)
+            if b:
+                target = label_at[b.group(2)]
+                if b.group(1):
+                    work.append((target, state))
+                    pc += 1
+                else:
+                    pc = target
+                continue
+            w = re.search(r"s_waitcnt.*vmcnt\((\d+)\)", l)
+            if w:
+                state = tuple(a for a in state if a < int(w.group(1)))
+            elif l == "s_barrier":
+                assert len(state) <= per_tile, "%s: barrier passed with %d loads-to-LDS in flight" % (name, len(state))
+                barriers += 1
+            elif re.match(r"(buffer|global|flat|scratch)_(load|store|atomic)", l):
+                state = tuple(min(a + 1, 64) for a in state)
+                if re.match(r"buffer_load_dwordx4 .* lds$", l):
+                    assert lines[pc - 1].startswith("s_mov_b32 m0,"), "%s: load-to-LDS without its M0 setup" % name
+                    state = state + (0,)
+            pc += 1
+    assert ends >= 1 and barriers >= 2
+    return len(seen)
+
+
+@pytest.fixture(scope="module")
+def lds_asm():
+    return compile_to_asm(LDS_SRC)
+
+
+def lds_kernel_names(asm):
+    return sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_122conv_stream_lds_kernelI\S+?):", asm, re.M)))
+
+
+def test_staged_input_kernel_waits(lds_asm):
+    names = lds_kernel_names(lds_asm)
+    assert len(names) == 4
+    for name in names:
+        lines = instructions(lds_asm, name)
+        n_loads = sum(1 for l in lines if re.match(r"buffer_load_dwordx4 .* lds$", l))
+        assert n_loads % 7 == 0 and n_loads >= 28, (name, n_loads)   # 7 per wave and tile: two tiles in the prologue, one per loop body
+        assert walk_lds_loads(lines, name, 7) > 10
+        others = [l for l in lines if re.search(r"\bm0\b", l) and not l.startswith("s_mov_b32 m0,")]
+        assert not others, (name, others[:3])        # M0 is written behind the compiler's back: nothing else may use it
+
+
+@pytest.mark.parametrize("mutation", ["weak_wait", "drop_store", "no_drain", "no_m0"])
+def test_staged_input_walker_catches_planted_mistakes(lds_asm, mutation):
+    name = lds_kernel_names(lds_asm)[0]
+    lines = instructions(lds_asm, name)
+    walk_lds_loads(lines, name, 7)
+    bad = list(lines)
+    if mutation == "weak_wait":
+        for i, l in enumerate(bad):
+            if re.match(r"s_waitcnt vmcnt\(11\)$", l):
+                bad[i] = "s_waitcnt vmcnt(12)"
+    elif mutation == "drop_store":
+        for i, l in enumerate(bad):          # one store fewer per tile: the count no longer covers the tile's loads
+            if l.startswith("buffer_store_dwordx4") and "nt" in l:
+                bad[i] = "s_nop 0"
+                break
+        # the loop bodies hold the other stores; drop one in each run of four
+        runs = [i for i, l in enumerate(bad) if l.startswith("buffer_store_dwordx4")]
+        for i in runs[::4]:
+            bad[i] = "s_nop 0"
+    elif mutation == "no_drain":
+        drains = [i for i, l in enumerate(bad) if re.match(r"s_waitcnt vmcnt\(0\)$", l)]
+        for i in drains[1:]:
+            bad[i] = "s_nop 0"
+    else:
+        first = next(i for i, l in enumerate(bad) if re.match(r"buffer_load_dwordx4 .* lds$", l))
+        bad[first - 1] = "s_nop 0"
+    with pytest.raises(AssertionError):
+        walk_lds_loads(bad, name, 7)
