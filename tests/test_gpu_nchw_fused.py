@@ -143,6 +143,36 @@ def test_channels_first_layer_runner(fc, oracle, axis):
     assert rel_l2_per_image(f64(y.cpu()), ref) <= TOL["f16"]
 
 
+def test_fused_nchw_under_graph_capture(fc):
+    """The library allocates nothing and never synchronises, so the call can be captured; every replay
+    (with eager work and synchronisations between them) equals the eager result."""
+    dt = torch.float16
+    plan = fc.foldconv_plan_nchw(4, 3, 40, 64, 64, 3, 3, 1, 16, fc.FOLD_W, dt)
+    s = plan.shapes
+    x = draw((4, 3, 40, 64), "f16", 71)
+    w = (draw((64, 3, 3, 3), "f16", 72) * 0.2).to(dt)
+    b = draw((64,), "f16", 73).cuda()
+    xf, w_exp, ws = prepare(fc, plan, x, w)
+    fc.foldconv_pack_filter(plan, w_exp, ws)
+    flags = fc.FLAG_OUT_NCHW | fc.FLAG_FILTER_PACKED | fc.FLAG_RELU
+    y = torch.zeros(s.y_bytes // 2, dtype=dt, device="cuda")
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        fc.foldconv_forward(plan, xf, w_exp, b, y, ws, flags, stream=st)
+    want = torch.zeros_like(y)
+    fc.foldconv_forward(plan, xf, w_exp, b, want, ws, flags)
+    torch.cuda.synchronize()
+    assert float(want.float().abs().sum()) > 0
+    for _ in range(3):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), want.view(torch.int16))
+
+
 def test_fused_nchw_refusals(fc):
     dt = torch.float16
     # geometries the fused kernel does not serve report it in the plan and are refused by the call
