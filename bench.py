@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the folded convolution on the headline layer from rocprofv3 counters
 # (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 0.999 + FETCH_SIZE x 1.998).  Set to None whenever
 # the convolution kernel changes after the counters were taken.
-MEASURED_TRAFFIC_BYTES = 431.6e6
+MEASURED_TRAFFIC_BYTES = None
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 
 

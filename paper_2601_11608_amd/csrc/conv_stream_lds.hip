@@ -52,11 +52,12 @@ constexpr unsigned kOutOfRangeL = 0x80000000u;  // beyond any resource extent us
 
 struct LdsArgs {
     unsigned MT;          // number of 32-pixel M tiles
-    unsigned J;           // M tiles in flight per partition = stride of a workgroup's tile walk
-    unsigned parts;       // 1, or 8: one contiguous range of M tiles per XCD (workgroup b runs on XCD b % 8)
-    unsigned TPP;         // M tiles per partition
+    unsigned J;           // M tiles in flight per XCD
+    unsigned parts;       // 1, or 8: M tiles are dealt to the XCDs in chunks (workgroup b runs on XCD b % 8)
+    unsigned CH;          // M tiles per chunk (divides J); chunk c belongs to XCD c % parts
+    unsigned stride;      // parts * J: the constant stride of a workgroup's tile walk
     int CQ;               // groups of 256 output columns (one workgroup each per tile)
-    unsigned dW, dH;      // the walk stride of 32*J pixels: folded columns and rows (mod the output height) moved
+    unsigned dW, dH;      // the walk stride of 32*stride pixels: folded columns and rows (mod the output height) moved
     int stepCol, wrapCol; // element column moved per step (dW*FC), and taken back when the folded column wraps (Wf_out*FC)
     unsigned stepOff, carryW, carryH;  // byte offset in x' moved per step, and the corrections of the two carries
     unsigned x_bytes;
@@ -90,8 +91,11 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     const int cq = (int)(wgp % (unsigned)a.CQ);
     const unsigned j0 = wgp / (unsigned)a.CQ;
     if (j0 >= a.J) return;  // workgroup-uniform
-    const unsigned t_first = part * a.TPP;
-    const unsigned t_end = t_first + a.TPP < a.MT ? t_first + a.TPP : a.MT;
+    // Chunks of CH consecutive tiles go to the XCDs in turn: neighbouring tiles share input rows inside
+    // one L2, and the 8 XCDs together write one compact region of y that moves through memory once.
+    const unsigned jc = j0 / a.CH;
+    const unsigned t_first = (a.parts * jc + part) * a.CH + (j0 - jc * a.CH);  // the workgroup's first tile
+    const unsigned t_end = a.MT;
     const int n_lo = (cq * 4 + wave) * COLS;
 
     // ---- filter fragments for the whole K extent, resident for the kernel's lifetime ----
@@ -147,7 +151,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     // Walk state of this lane's pixel (pixel r of the tile requested next), kept incrementally: a
     // tile step is a constant number of pixels, so folded column, row and element offset move by
     // constants plus two carries; no multiplication or division inside the loop.
-    unsigned p_m = (t_first + j0) * 32u + (unsigned)r;  // pixel index
+    unsigned p_m = t_first * 32u + (unsigned)r;  // pixel index
     unsigned p_wo = p_m % (unsigned)g.Wf_out, p_ho;     // folded column, output row
     unsigned p_off2;  // byte offset of x'[img][ho][wo] + the lane's chunk at e_min (may wrap below zero at the left edge)
     int p_col;        // element column of that chunk inside the input row
@@ -159,13 +163,13 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
         p_off2 = 2u * (unsigned)((int)((img * (unsigned)g.H + p_ho) * (unsigned)g.in_row) + p_col);
     }
     int ld_stage = 0;
-    unsigned ld_tile = t_first + j0;
+    unsigned ld_tile = t_first;
     int ld_vm = 0;         // this lane's pixel of the tile being requested exists
     unsigned ld_dst0 = 0;  // LDS address of this wave's first fragment in the tile's stage
     auto request_begin = [&]() {
         // false for tiles past the end of the walk: every lane out of range, zeros deposited, no traffic
         ld_vm = (int)(ld_tile < t_end) & (int)(p_m < (unsigned)g.M);
-        ld_tile += a.J;
+        ld_tile += a.stride;
         ld_dst0 = lds_base + (unsigned)(ld_stage * STAGE + wave * FRAG);
         ld_stage = ld_stage + 1 == NSTAGE ? 0 : ld_stage + 1;
     };
@@ -179,7 +183,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
         asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(dst), "v"(voff), "s"(xr) : "memory");
     };
     auto request_end = [&]() {  // step the walk state to the next tile of this workgroup
-        p_m += a.J * 32u;
+        p_m += a.stride * 32u;
         p_wo += a.dW;
         const bool c1 = p_wo >= (unsigned)g.Wf_out;
         p_wo -= c1 ? (unsigned)g.Wf_out : 0u;
@@ -193,7 +197,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     // ---- epilogue of one tile, in pieces that are slotted between the MFMAs of the next tile ----
     // two accumulator sets trade places every tile: one is accumulated, the other (finished) is stored
     floatx16_t acc_a[NT], acc_b[NT];
-    unsigned m0 = (t_first + j0) * 32u;  // first pixel of the tile being accumulated
+    unsigned m0 = t_first * 32u;  // first pixel of the tile being accumulated
     unsigned d_m0 = 0;                   // ... of the finished tile
     int d_valid = 0;                             // 0: nothing finished yet, its stores are dropped
     __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, 0, 0x00020000);
@@ -291,17 +295,17 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
             __builtin_amdgcn_sched_barrier(0);
         }
         d_m0 = m0, d_valid = 1;  // this tile is finished; its epilogue rides along with the next one
-        m0 += a.J * 32u;
+        m0 += a.stride * 32u;
     };
     bool last_in_a = false;
-    for (unsigned mt = t_first + j0; mt < t_end;) {
+    for (unsigned mt = t_first; mt < t_end;) {
         tile(acc_a, acc_b);
         last_in_a = true;
-        mt += a.J;
+        mt += a.stride;
         if (mt >= t_end) break;
         tile(acc_b, acc_a);
         last_in_a = false;
-        mt += a.J;
+        mt += a.stride;
     }
     // the last tile's epilogue (dropped if the workgroup had no tile)
     if (last_in_a) {
@@ -322,12 +326,20 @@ int launch_inst(const ConvGeom &g, const void *x, const void *wp, const void *bi
     a.MT = (unsigned)((g.M + 31) / 32);
     a.CQ = g.NCo / 256;
     a.parts = a.MT >= 64 * 8 ? 8 : 1;
-    a.TPP = (a.MT + a.parts - 1) / a.parts;
+    const long long tpp = (a.MT + a.parts - 1) / a.parts;
     long long J = (256 / a.parts) / a.CQ;  // one workgroup per compute unit
     if (J < 1) J = 1;
-    if (J > a.TPP) J = a.TPP;
+    if (J > tpp) J = tpp;
+    long long CH = 1;
+    if (a.parts > 1) {
+        CH = 2;
+        while (CH > J) CH /= 2;
+        J -= J % CH;
+    }
     a.J = (unsigned)J;
-    const long long S = J * 32, plane = (long long)g.Hout * g.Wf_out;
+    a.CH = (unsigned)CH;
+    a.stride = (unsigned)(J * a.parts);
+    const long long S = (long long)a.stride * 32, plane = (long long)g.Hout * g.Wf_out;
     const long long dI = S / plane;
     a.dH = (unsigned)((S % plane) / g.Wf_out);
     a.dW = (unsigned)((S % plane) % g.Wf_out);

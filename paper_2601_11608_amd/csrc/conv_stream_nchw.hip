@@ -46,9 +46,9 @@ constexpr unsigned kOutOfRangeN = 0xfffffff0u;  // beyond any resource extent us
 
 struct NchwArgs {
     unsigned MT;          // 32-pixel M tiles
-    unsigned per_xcd;     // tiles per XCD partition (workgroup b runs on XCD b % 8)
-    unsigned wg_per_xcd;  // workgroups per partition = stride of a workgroup's tile walk
-    unsigned dW, dH, dI;  // that stride of 32*wg_per_xcd pixels as (folded column, row, image) steps
+    unsigned CH;          // tiles per chunk; chunk c belongs to XCD c % 8 (workgroup b runs on XCD b % 8)
+    unsigned wg_per_xcd;  // workgroups per XCD (a multiple of CH); a workgroup's tile walk strides by 8 times that
+    unsigned dW, dH, dI;  // that stride of 32*8*wg_per_xcd pixels as (folded column, row, image) steps
     unsigned mgW, mgH;    // ceil(2^32 / Wf_out), ceil(2^32 / Hout)
     unsigned x_bytes, y_bytes;
     int ksteps;           // 16-wide K-steps per kh actually walked (<= KSM)
@@ -153,13 +153,15 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     const int rd_off = sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;  // + k * C_out * 2 per slot
     const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;             // bytes per channel plane
 
-    // tiles of this workgroup: its XCD's contiguous range, strided by the workgroups of that XCD
+    // Tiles are dealt to the XCDs in chunks of CH consecutive tiles, chunk c to XCD c % 8 (neighbouring
+    // tiles share input rows inside one L2, and the 8 XCDs together write one compact, moving region
+    // of y).  The workgroups of an XCD hold wg_per_xcd/CH chunks, 8 chunks apart.
     const unsigned xcd = blockIdx.x % 8u, wg = blockIdx.x / 8u;
-    const unsigned t_first = xcd * a.per_xcd;
-    const unsigned t_end = t_first + a.per_xcd < a.MT ? t_first + a.per_xcd : a.MT;
+    const unsigned wc = wg / a.CH;
+    const unsigned t_first = (8u * wc + xcd) * a.CH + (wg - wc * a.CH);  // the workgroup's first tile
 
     // first pixel of the workgroup's current tile, advanced incrementally
-    unsigned m0 = (t_first + wg) * 32u;
+    unsigned m0 = t_first * 32u;
     unsigned wo0 = m0 % (unsigned)g.Wf_out, ho0, img0;
     {
         const unsigned rowid = m0 / (unsigned)g.Wf_out;
@@ -177,7 +179,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         img = img_base + q2;
     };
     auto advance = [&]() {
-        m0 += a.wg_per_xcd * 32u;
+        m0 += a.wg_per_xcd * 256u;
         wo0 += a.dW;
         unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
         wo0 -= c * (unsigned)g.Wf_out;
@@ -216,7 +218,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     // issued ahead of the four stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int buf = 0;
-    for (unsigned mt = t_first + wg; mt < t_end; mt += a.wg_per_xcd) {
+    for (unsigned mt = t_first; mt < a.MT; mt += 8u * a.wg_per_xcd) {
         floatx16_t acc[NT];
         floatx16_t zero;
 #pragma unroll
@@ -318,10 +320,14 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
     a.MT = (unsigned)((g.M + 31) / 32);
-    a.per_xcd = (a.MT + 7) / 8;
+    const unsigned per_xcd = (a.MT + 7) / 8;
     a.wg_per_xcd = 32u * per_cu;
-    if (a.wg_per_xcd > a.per_xcd) a.wg_per_xcd = a.per_xcd;
-    const long long S = 32LL * a.wg_per_xcd, plane = (long long)g.Hout * g.Wf_out;
+    if (a.wg_per_xcd > per_xcd) a.wg_per_xcd = per_xcd;
+    // chunk: a few input rows' worth of tiles (the rows a chunk shares with its neighbours are fetched into two L2s)
+    a.CH = 2;
+    while (a.CH < 8 && g.KH > 1 && 32 * a.CH < 4u * (unsigned)g.Wf_out) a.CH *= 2;
+    while (a.CH > 1 && (a.wg_per_xcd % a.CH != 0 || a.MT < 32 * a.CH)) a.CH /= 2;
+    const long long S = 256LL * a.wg_per_xcd, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
     a.dW = (unsigned)((S % plane) % g.Wf_out);
