@@ -384,7 +384,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     long long CH = 1;
     if (a.parts > 1) {
         CH = 2;
-        while (CH < 8 && g.KH > 1 && 32 * CH < 4LL * g.Wf_out) CH *= 2;
+        while (g.KH > 1 && 32 * CH < 4LL * g.Wf_out) CH *= 2;  // four output rows or more
         while (CH > J) CH /= 2;
         J -= J % CH;
     }

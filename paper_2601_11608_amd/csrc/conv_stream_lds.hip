@@ -333,6 +333,7 @@ int launch_inst(const ConvGeom &g, const void *x, const void *wp, const void *bi
     long long CH = 1;
     if (a.parts > 1) {
         CH = 2;
+        while (32 * CH < 4LL * g.Wf_out) CH *= 2;  // four output rows or more
         while (CH > J) CH /= 2;
         J -= J % CH;
     }

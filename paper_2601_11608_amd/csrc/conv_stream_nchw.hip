@@ -325,7 +325,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     if (a.wg_per_xcd > per_xcd) a.wg_per_xcd = per_xcd;
     // chunk: a few input rows' worth of tiles (the rows a chunk shares with its neighbours are fetched into two L2s)
     a.CH = 2;
-    while (a.CH < 8 && g.KH > 1 && 32 * a.CH < 4u * (unsigned)g.Wf_out) a.CH *= 2;
+    while (a.CH < 32 && g.KH > 1 && 32 * a.CH < 4u * (unsigned)g.Wf_out) a.CH *= 2;  // four output rows or more
     while (a.CH > 1 && (a.wg_per_xcd % a.CH != 0 || a.MT < 32 * a.CH)) a.CH /= 2;
     const long long S = 256LL * a.wg_per_xcd, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
