@@ -25,9 +25,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the folded convolution on the headline layer from rocprofv3 counters
-# (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 0.999 + FETCH_SIZE x 1.998).  Set to None whenever
+# (profiles/conv_stream_c2_fp16.md: WRITE_SIZE x 1.000 + FETCH_SIZE x 1.998).  Set to None whenever
 # the convolution kernel changes after the counters were taken.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 439.2e6
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 
 
