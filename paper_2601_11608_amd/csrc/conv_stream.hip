@@ -63,10 +63,7 @@ __device__ __forceinline__ void static_for(F &&f) {
 
 struct StreamArgs {
     unsigned MT;        // number of 32-pixel M tiles
-    unsigned J;         // M tiles in flight per XCD
-    unsigned parts;     // 1, or 8: M tiles are dealt to the XCDs in chunks (workgroup b runs on XCD b % 8)
-    unsigned CH;        // M tiles per chunk (divides J); chunk c belongs to XCD c % parts
-    unsigned stride;    // parts * J: the constant stride of a wave's M-tile walk
+    FcDeal deal;        // how M tiles are dealt to the XCDs; deal.stride is the stride of a wave's M-tile walk
     int NG;             // column groups of NT*32 columns
     int ksteps;         // 16-wide K-steps per kh actually walked (<= KSM)
     unsigned dW, dH, dI;  // the walk stride of 32*stride pixels as (folded column, row, image) steps
@@ -100,20 +97,13 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     const int r = lane & 31, hf = lane >> 5;
     unsigned char *slab = lds_all + wave * SLAB;
 
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  M tiles go to the
-    // XCDs in chunks of CH consecutive tiles, chunk c to XCD c % 8: neighbouring tiles share
-    // their input rows inside one L2, and at any moment the 8 XCDs together write one compact
-    // region of y that moves through memory once (one contiguous range of tiles per XCD instead
-    // means eight write fronts far apart, which the memory system serves 10 % slower).
-    // The J tiles an XCD has in flight are J/CH chunks, `parts` chunks apart; every wave then
-    // strides by parts*J tiles.
-    const unsigned part = blockIdx.x % a.parts;
-    const unsigned gw = (blockIdx.x / a.parts) * 4 + wave;
+    // Workgroups are dealt round-robin to the 8 XCDs; M tiles follow them in chunks (FcDeal).
+    const unsigned part = blockIdx.x % a.deal.parts;
+    const unsigned gw = (blockIdx.x / a.deal.parts) * 4 + wave;
     const int ng = (int)(gw % (unsigned)a.NG);
     const unsigned j0 = gw / (unsigned)a.NG;
-    if (j0 >= a.J) return;  // wave-uniform
-    const unsigned jc = j0 / a.CH;
-    const unsigned t_first = (a.parts * jc + part) * a.CH + (j0 - jc * a.CH);  // the wave's first tile
+    if (j0 >= a.deal.J) return;  // wave-uniform
+    const unsigned t_first = fc_deal_first_tile(a.deal, part, j0);  // the wave's first tile
 
     const int KH = EXACT ? KHM : g.KH;
     const int KS = EXACT ? KSM : a.ksteps;
@@ -239,7 +229,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         }
     };
     auto advance = [&]() {
-        m0 += a.stride * 32u;
+        m0 += a.deal.stride * 32u;
         wo0 += a.dW;
         unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
         wo0 -= c * (unsigned)g.Wf_out;
@@ -256,7 +246,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     // issued ahead of PASSES stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    for (unsigned mt = t_first; mt < a.MT; mt += a.stride) {
+    for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
         floatx16_t acc[NT];
         floatx16_t zero;
 #pragma unroll
@@ -373,25 +363,11 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
         resident = nb > 2 ? 2 : nb;
     }
     const int per_cu = resident;
-    a.parts = a.MT >= 64 * 8 ? 8 : 1;  // deal tiles per XCD unless there are too few tiles to split
-    const long long tpp = (a.MT + a.parts - 1) / a.parts;
-    long long waves = 256LL * per_cu * 4 / a.parts;  // per XCD
-    long long J = waves / a.NG;
-    if (J < 1) J = 1;
-    if (J > tpp) J = tpp;
-    // Chunk: a few input rows' worth of tiles, so that the rows a chunk shares with its neighbours
-    // (fetched into two L2s) stay a small part of what it reads.
-    long long CH = 1;
-    if (a.parts > 1) {
-        CH = 2;
-        while (g.KH > 1 && 32 * CH < 4LL * g.Wf_out) CH *= 2;  // four output rows or more
-        while (CH > J) CH /= 2;
-        J -= J % CH;
-    }
-    a.J = (unsigned)J;
-    a.CH = (unsigned)CH;
-    a.stride = (unsigned)(J * a.parts);
-    const long long S = (long long)a.stride * 32, plane = (long long)g.Hout * g.Wf_out;
+    const unsigned parts = a.MT >= 64 * 8 ? 8 : 1;  // deal tiles per XCD unless there are too few tiles to split
+    const unsigned waves = 256u * (unsigned)per_cu * 4u / parts;  // per XCD
+    a.deal = fc_make_deal(a.MT, parts, waves / (unsigned)a.NG, g.KH, g.Wf_out);
+    const long long J = a.deal.J;
+    const long long S = (long long)a.deal.stride * 32, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
     a.dW = (unsigned)((S % plane) % g.Wf_out);
@@ -399,7 +375,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.mgH = magic_for((unsigned)g.Hout);
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.linear_out = g.out_row == g.Wf_out * g.NCo ? 1 : 0;
-    const unsigned blocks = (unsigned)((J * a.NG + 3) / 4) * a.parts;
+    const unsigned blocks = (unsigned)((J * a.NG + 3) / 4) * a.deal.parts;
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                       \
     conv_stream_kernel<TR, NT, KHM, KSM, OCC, EX, RL><<<blocks, 256, 0, st>>>(              \

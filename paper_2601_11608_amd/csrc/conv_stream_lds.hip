@@ -52,10 +52,7 @@ constexpr unsigned kOutOfRangeL = 0x80000000u;  // beyond any resource extent us
 
 struct LdsArgs {
     unsigned MT;          // number of 32-pixel M tiles
-    unsigned J;           // M tiles in flight per XCD
-    unsigned parts;       // 1, or 8: M tiles are dealt to the XCDs in chunks (workgroup b runs on XCD b % 8)
-    unsigned CH;          // M tiles per chunk (divides J); chunk c belongs to XCD c % parts
-    unsigned stride;      // parts * J: the constant stride of a workgroup's tile walk
+    FcDeal deal;          // how M tiles are dealt to the XCDs; deal.stride is the stride of a workgroup's tile walk
     int CQ;               // groups of 256 output columns (one workgroup each per tile)
     unsigned dW, dH;      // the walk stride of 32*stride pixels: folded columns and rows (mod the output height) moved
     int stepCol, wrapCol; // element column moved per step (dW*FC), and taken back when the folded column wraps (Wf_out*FC)
@@ -86,15 +83,13 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     const int r = lane & 31, hf = lane >> 5;
     unsigned char *slab = lds + NSTAGE * STAGE + wave * SLAB;
 
-    const unsigned part = blockIdx.x % a.parts;
-    const unsigned wgp = blockIdx.x / a.parts;
+    const unsigned part = blockIdx.x % a.deal.parts;
+    const unsigned wgp = blockIdx.x / a.deal.parts;
     const int cq = (int)(wgp % (unsigned)a.CQ);
     const unsigned j0 = wgp / (unsigned)a.CQ;
-    if (j0 >= a.J) return;  // workgroup-uniform
-    // Chunks of CH consecutive tiles go to the XCDs in turn: neighbouring tiles share input rows inside
-    // one L2, and the 8 XCDs together write one compact region of y that moves through memory once.
-    const unsigned jc = j0 / a.CH;
-    const unsigned t_first = (a.parts * jc + part) * a.CH + (j0 - jc * a.CH);  // the workgroup's first tile
+    if (j0 >= a.deal.J) return;  // workgroup-uniform
+    // Workgroup b runs on XCD b % 8; M tiles follow the workgroups in chunks (FcDeal).
+    const unsigned t_first = fc_deal_first_tile(a.deal, part, j0);  // the workgroup's first tile
     const unsigned t_end = a.MT;
     const int n_lo = (cq * 4 + wave) * COLS;
 
@@ -169,7 +164,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     auto request_begin = [&]() {
         // false for tiles past the end of the walk: every lane out of range, zeros deposited, no traffic
         ld_vm = (int)(ld_tile < t_end) & (int)(p_m < (unsigned)g.M);
-        ld_tile += a.stride;
+        ld_tile += a.deal.stride;
         ld_dst0 = lds_base + (unsigned)(ld_stage * STAGE + wave * FRAG);
         ld_stage = ld_stage + 1 == NSTAGE ? 0 : ld_stage + 1;
     };
@@ -183,7 +178,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
         asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(dst), "v"(voff), "s"(xr) : "memory");
     };
     auto request_end = [&]() {  // step the walk state to the next tile of this workgroup
-        p_m += a.stride * 32u;
+        p_m += a.deal.stride * 32u;
         p_wo += a.dW;
         const bool c1 = p_wo >= (unsigned)g.Wf_out;
         p_wo -= c1 ? (unsigned)g.Wf_out : 0u;
@@ -295,17 +290,17 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
             __builtin_amdgcn_sched_barrier(0);
         }
         d_m0 = m0, d_valid = 1;  // this tile is finished; its epilogue rides along with the next one
-        m0 += a.stride * 32u;
+        m0 += a.deal.stride * 32u;
     };
     bool last_in_a = false;
     for (unsigned mt = t_first; mt < t_end;) {
         tile(acc_a, acc_b);
         last_in_a = true;
-        mt += a.stride;
+        mt += a.deal.stride;
         if (mt >= t_end) break;
         tile(acc_b, acc_a);
         last_in_a = false;
-        mt += a.stride;
+        mt += a.deal.stride;
     }
     // the last tile's epilogue (dropped if the workgroup had no tile)
     if (last_in_a) {
@@ -325,22 +320,10 @@ int launch_inst(const ConvGeom &g, const void *x, const void *wp, const void *bi
     LdsArgs a;
     a.MT = (unsigned)((g.M + 31) / 32);
     a.CQ = g.NCo / 256;
-    a.parts = a.MT >= 64 * 8 ? 8 : 1;
-    const long long tpp = (a.MT + a.parts - 1) / a.parts;
-    long long J = (256 / a.parts) / a.CQ;  // one workgroup per compute unit
-    if (J < 1) J = 1;
-    if (J > tpp) J = tpp;
-    long long CH = 1;
-    if (a.parts > 1) {
-        CH = 2;
-        while (32 * CH < 4LL * g.Wf_out) CH *= 2;  // four output rows or more
-        while (CH > J) CH /= 2;
-        J -= J % CH;
-    }
-    a.J = (unsigned)J;
-    a.CH = (unsigned)CH;
-    a.stride = (unsigned)(J * a.parts);
-    const long long S = (long long)a.stride * 32, plane = (long long)g.Hout * g.Wf_out;
+    const unsigned parts = a.MT >= 64 * 8 ? 8 : 1;
+    a.deal = fc_make_deal(a.MT, parts, (256u / parts) / (unsigned)a.CQ, g.KH, g.Wf_out);  // one workgroup per compute unit
+    const long long J = a.deal.J;
+    const long long S = (long long)a.deal.stride * 32, plane = (long long)g.Hout * g.Wf_out;
     const long long dI = S / plane;
     a.dH = (unsigned)((S % plane) / g.Wf_out);
     a.dW = (unsigned)((S % plane) % g.Wf_out);
@@ -352,7 +335,7 @@ int launch_inst(const ConvGeom &g, const void *x, const void *wp, const void *bi
     a.carryW = (unsigned)(2 * ((long long)g.in_row - (long long)g.Wf_out * g.FC));
     a.carryH = (unsigned)(2 * ((long long)(g.H - g.Hout) * g.in_row));
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
-    const unsigned blocks = (unsigned)(J * a.CQ) * a.parts;
+    const unsigned blocks = (unsigned)(J * a.CQ) * a.deal.parts;
     if (g.relu)
         conv_stream_lds_kernel<TR, KHM, QM, true><<<blocks, 256, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     else

@@ -46,9 +46,8 @@ constexpr unsigned kOutOfRangeN = 0xfffffff0u;  // beyond any resource extent us
 
 struct NchwArgs {
     unsigned MT;          // 32-pixel M tiles
-    unsigned CH;          // tiles per chunk; chunk c belongs to XCD c % 8 (workgroup b runs on XCD b % 8)
-    unsigned wg_per_xcd;  // workgroups per XCD (a multiple of CH); a workgroup's tile walk strides by 8 times that
-    unsigned dW, dH, dI;  // that stride of 32*8*wg_per_xcd pixels as (folded column, row, image) steps
+    FcDeal deal;          // how M tiles are dealt to the XCDs: deal.J workgroups per XCD, one tile each at a time
+    unsigned dW, dH, dI;  // the stride of a workgroup's tile walk, 32*deal.stride pixels, as (folded column, row, image) steps
     unsigned mgW, mgH;    // ceil(2^32 / Wf_out), ceil(2^32 / Hout)
     unsigned x_bytes, y_bytes;
     int ksteps;           // 16-wide K-steps per kh actually walked (<= KSM)
@@ -153,12 +152,9 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     const int rd_off = sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;  // + k * C_out * 2 per slot
     const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;             // bytes per channel plane
 
-    // Tiles are dealt to the XCDs in chunks of CH consecutive tiles, chunk c to XCD c % 8 (neighbouring
-    // tiles share input rows inside one L2, and the 8 XCDs together write one compact, moving region
-    // of y).  The workgroups of an XCD hold wg_per_xcd/CH chunks, 8 chunks apart.
+    // Workgroup b runs on XCD b % 8; M tiles follow the workgroups in chunks (FcDeal).
     const unsigned xcd = blockIdx.x % 8u, wg = blockIdx.x / 8u;
-    const unsigned wc = wg / a.CH;
-    const unsigned t_first = (8u * wc + xcd) * a.CH + (wg - wc * a.CH);  // the workgroup's first tile
+    const unsigned t_first = fc_deal_first_tile(a.deal, xcd, wg);  // the workgroup's first tile
 
     // first pixel of the workgroup's current tile, advanced incrementally
     unsigned m0 = t_first * 32u;
@@ -179,7 +175,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         img = img_base + q2;
     };
     auto advance = [&]() {
-        m0 += a.wg_per_xcd * 256u;
+        m0 += a.deal.stride * 32u;
         wo0 += a.dW;
         unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
         wo0 -= c * (unsigned)g.Wf_out;
@@ -218,7 +214,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     // issued ahead of the four stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int buf = 0;
-    for (unsigned mt = t_first; mt < a.MT; mt += 8u * a.wg_per_xcd) {
+    for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
         floatx16_t acc[NT];
         floatx16_t zero;
 #pragma unroll
@@ -320,14 +316,8 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
     a.MT = (unsigned)((g.M + 31) / 32);
-    const unsigned per_xcd = (a.MT + 7) / 8;
-    a.wg_per_xcd = 32u * per_cu;
-    if (a.wg_per_xcd > per_xcd) a.wg_per_xcd = per_xcd;
-    // chunk: a few input rows' worth of tiles (the rows a chunk shares with its neighbours are fetched into two L2s)
-    a.CH = 2;
-    while (a.CH < 32 && g.KH > 1 && 32 * a.CH < 4u * (unsigned)g.Wf_out) a.CH *= 2;  // four output rows or more
-    while (a.CH > 1 && (a.wg_per_xcd % a.CH != 0 || a.MT < 32 * a.CH)) a.CH /= 2;
-    const long long S = 256LL * a.wg_per_xcd, plane = (long long)g.Hout * g.Wf_out;
+    a.deal = fc_make_deal(a.MT, 8, 32u * per_cu, g.KH, g.Wf_out);
+    const long long S = 32LL * a.deal.stride, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
     a.dW = (unsigned)((S % plane) % g.Wf_out);
@@ -336,7 +326,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
-    const unsigned blocks = a.wg_per_xcd * 8;
+    const unsigned blocks = a.deal.J * 8;
     auto go = [&](auto kernel) {
         // more than 64 KB of dynamic LDS has to be allowed per kernel, once
         static bool allowed = false;  // benign race: every thread sets the same attribute

@@ -81,6 +81,47 @@ FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
 FC_HD int fc_gcd8(int c) { return (c % 8 == 0) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
 FC_HD int fc_compact_phases(const ConvGeom &g) { return 8 / g.cgcd; }
 
+// How the persistent streaming kernels deal their 32-pixel M tiles to the 8 XCDs (workgroup b runs
+// on XCD b % 8, each XCD has its own L2).  Tiles go out in chunks of CH consecutive tiles, chunk c
+// to XCD c % parts: neighbouring tiles share their input rows inside one L2, and at any moment the
+// XCDs together write one compact region of y that moves through memory once (one contiguous range
+// of tiles per XCD instead means eight write fronts far apart, which the memory system serves
+// about 10 % slower).  An XCD holds J tiles at a time, as J/CH chunks that are `parts` chunks
+// apart; slot j0 < J of XCD `part` starts at fc_deal_first_tile and then strides by parts*J tiles,
+// so every tile below MT is visited exactly once.
+struct FcDeal {
+    unsigned parts;   // 1 (too few tiles to split), or 8
+    unsigned CH;      // tiles per chunk, divides J
+    unsigned J;       // tiles in flight per XCD
+    unsigned stride;  // parts * J
+};
+// slots: how many tiles one XCD's resident waves (or workgroups) can hold at a time.
+FC_HD FcDeal fc_make_deal(unsigned MT, unsigned parts, unsigned slots, int KH, int Wf_out) {
+    FcDeal d;
+    d.parts = parts;
+    const unsigned tpp = (MT + parts - 1) / parts;
+    unsigned J = slots < 1 ? 1 : slots;
+    if (J > tpp) J = tpp;
+    if (J < 1) J = 1;
+    unsigned CH = 1;
+    if (parts > 1) {
+        // a chunk spans four output rows or more: the rows it shares with its neighbours (fetched
+        // into two L2s) stay a small part of what it reads
+        CH = 2;
+        while (KH > 1 && CH < 1024 && 32ll * CH < 4ll * Wf_out) CH *= 2;
+        while (CH > J || (CH > 1 && MT < 4 * parts * CH)) CH /= 2;
+        J -= J % CH;
+    }
+    d.CH = CH;
+    d.J = J;
+    d.stride = J * parts;
+    return d;
+}
+FC_HD unsigned fc_deal_first_tile(const FcDeal &d, unsigned part, unsigned j0) {
+    const unsigned jc = j0 / d.CH;
+    return (d.parts * jc + part) * d.CH + (j0 - jc * d.CH);
+}
+
 enum { FC_KERNEL_GATHER = 0, FC_KERNEL_TILED = 1, FC_KERNEL_STREAM = 2 };
 
 struct foldconv_plan_s {
