@@ -3,10 +3,10 @@
 // there the matrix cores, not HBM, bound the layer.
 //
 // One workgroup of 2 x WM waves computes a BN (output columns n) x BM (folded
-// output pixels m) tile of y'^T, BN = 128 or 256, BM = 64*WM (128 as built);
-// each wave a (BN/2) x 64 part as TN x 2 MFMA tiles of 32 x 32 (TN = 2 or 4: the
-// wider tile halves the LDS reads and the input re-reads per MFMA and is used when
-// there are enough output columns to fill it).  K = (kh, extended channel e) is walked in
+// output pixels m) tile of y'^T, BN = 128, 192 or 256, BM = 64*WM (128 as built);
+// each wave a (BN/2) x 64 part as TN x 2 MFMA tiles of 32 x 32 (TN = 2, 3 or 4: a
+// wider tile needs fewer LDS reads and input re-reads per MFMA but walks a wider band
+// and pads F*C_out further; the host picks the width that issues the least work).  K = (kh, extended channel e) is walked in
 // blocks of 32 elements (two MFMA K-steps), restricted to the band of w' that
 // can be non-zero for the tile's output slots (paper: Eq. "filter_construct";
 // off-band blocks are structural zeros) unless the dense walk is asked for.
@@ -396,11 +396,12 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
 
 template <typename TR>
 int launch_any(const ConvGeom &g, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    // A 256 x 256 tile on eight waves (WM = 4) moves a third fewer operand bytes per multiply but
-    // measured the same as 256 x 128 on the layers it fits, so only WM = 2 is instantiated.
     // WM = 4 (a 256 x 256 tile on eight waves, a third fewer operand bytes out of L2 per multiply)
     // measured the same as 256 x 128 on the one layer of the benchmark set it fits; not instantiated.
-    return fc_tiled_bn(g) == 256 ? launch<TR, 4, 2>(g, x, wp, bias, y, st) : launch<TR, 2, 2>(g, x, wp, bias, y, st);
+    const int bn = fc_tiled_bn(g);
+    if (bn == 256) return launch<TR, 4, 2>(g, x, wp, bias, y, st);
+    if (bn == 192) return launch<TR, 3, 2>(g, x, wp, bias, y, st);
+    return launch<TR, 2, 2>(g, x, wp, bias, y, st);
 }
 
 }  // namespace

@@ -6,7 +6,7 @@
 
 // --- kernel choice and its tiling facts (select.cpp) -------------------------
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt);
-int fc_band_tile_n(int kernel, const ConvGeom &g);  // output columns sharing one band window
+int fc_band_tile_n(int kernel, const ConvGeom &g);  // output columns sharing one band window (for g's walk, g.band)
 int fc_band_align(int kernel, foldconv_dtype_t dt); // alignment of the band window in elements
 
 // Shape of the streaming kernel instance for a geometry; false if none fits.
@@ -52,6 +52,6 @@ bool fc_stream_lds_ok(const ConvGeom &g);
 int fc_launch_conv_stream_lds(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,
                               const void *bias, void *y, void *stream);
 bool fc_tiled_ok(const ConvGeom &g);
-int fc_tiled_bn(const ConvGeom &g);  // output columns per workgroup tile of the tiled kernel: 128 or 256
+int fc_tiled_bn(const ConvGeom &g);  // output columns per workgroup tile of the tiled kernel for g's walk (g.band): 128, 192 or 256
 int fc_launch_conv_gather(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_exp, const void *bias,
                           void *y, void *stream);

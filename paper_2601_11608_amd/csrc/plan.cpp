@@ -143,9 +143,12 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
 
     const bool mfma16 = dtype != FOLDCONV_F32;
     const int kstep = mfma16 ? 16 : 2;
-    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g), kstep, fc_band_align(s.conv_kernel, dtype));
-    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g), kstep, fc_band_align(s.conv_kernel, dtype));
-    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q), kstep, fc_band_align(s.padded_kernel, dtype));
+    ConvGeom g_dense = g, g_band = g, q_band = q;  // the tile width may depend on the walk
+    g_dense.band = 0;
+    g_band.band = q_band.band = 1;
+    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g_dense), kstep, fc_band_align(s.conv_kernel, dtype));
+    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g_band), kstep, fc_band_align(s.conv_kernel, dtype));
+    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q_band), kstep, fc_band_align(s.padded_kernel, dtype));
 
     *out = p;
     return FOLDCONV_OK;

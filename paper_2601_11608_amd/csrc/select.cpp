@@ -37,9 +37,25 @@ static bool vector_ok(const ConvGeom &g) {
 bool fc_tiled_ok(const ConvGeom &g) { return vector_ok(g); }
 
 int fc_tiled_bn(const ConvGeom &g) {
-    // The 256-column tile when it wastes no more columns than the 128-column one would.
-    const int pad128 = (g.NCo + 127) / 128 * 128, pad256 = (g.NCo + 255) / 256 * 256;
-    return (g.NCo >= 256 && pad256 <= pad128) ? 256 : 128;
+    // Multiplies issued by a tile width = sum over its N tiles of (K blocks inside the tile's band
+    // window, or all of them for the dense walk) x (tile width).  A wider tile covers more output
+    // slots, hence a wider band window and more structural zeros multiplied, and it pads F*C_out
+    // further; but it moves fewer operand bytes per multiply and needs fewer workgroups.  The
+    // weights are the measured time per issued multiply relative to the 128-column tile.
+    static const struct { int bn; double weight; } kCand[] = {{128, 1.0}, {192, 0.93}, {256, 0.85}};
+    int best = 128;
+    double best_cost = 0.0;
+    for (const auto &c : kCand) {
+        double work = 0.0;
+        for (int n0 = 0; n0 < g.NCo; n0 += c.bn) {
+            int e_lo, e_hi;
+            fc_band_window(g, n0, n0 + c.bn, 8, &e_lo, &e_hi);
+            work += (double)((e_hi - e_lo + 31) / 32) * c.bn;
+        }
+        const double cost = work * c.weight;
+        if (best_cost == 0.0 || cost < best_cost) best = c.bn, best_cost = cost;
+    }
+    return best;
 }
 
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {

@@ -83,6 +83,8 @@ SMALL = [
     (1, 20, 28, 68, 32, 3, 3, 1, 4, True, True),    # several 128-pixel M tiles, ragged last one
     (1, 6, 16, 68, 64, 3, 3, 1, 4, True, True),     # NCo = 256: the 256-column tile of the tiled kernel
     (1, 20, 28, 132, 256, 3, 3, 1, 4, False, True), # NCo = 1024, several M tiles with a ragged last one
+    (1, 20, 28, 68, 132, 3, 3, 1, 4, True, True),   # NCo = 528: three 192-column tiles, the last one ragged, two M tiles
+    (2, 10, 28, 20, 36, 3, 3, 1, 4, False, True),   # NCo = 144 in one 192-column tile
     (2, 65, 1024, 3, 64, 3, 3, 1, 16, True, True),  # 8320 folded pixels, many tiles per wave of the streaming kernel
     (3, 50, 480, 12, 48, 3, 3, 1, 4, False, False), # same with NCo = 192 (3 column groups)
 ]

@@ -114,11 +114,11 @@ def loads_per_block(lines):
 
 def test_staging_loads_are_published_with_the_right_counts(asm):
     names = sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_117conv_tiled_kernelI\S+?):", asm, re.M)))
-    assert len(names) == 8
+    assert len(names) == 12
     for name in names:
         lines = instructions(asm, name)
         nl = loads_per_block(lines)
-        assert nl in (4, 6), (name, nl)
+        assert nl in (4, 5, 6), (name, nl)
         waits = [int(w) for l in lines for w in re.findall(r"s_waitcnt vmcnt\((\d+)\)$", l)]
         assert 0 in waits and waits.count(nl) >= 2, (name, waits)
         assert explore(lines, name, nl) > 10
