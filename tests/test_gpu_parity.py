@@ -87,6 +87,10 @@ SMALL = [
     (2, 10, 28, 20, 36, 3, 3, 1, 4, False, True),   # NCo = 144 in one 192-column tile
     (2, 65, 1024, 3, 64, 3, 3, 1, 16, True, True),  # 8320 folded pixels, many tiles per wave of the streaming kernel
     (3, 50, 480, 12, 48, 3, 3, 1, 4, False, False), # same with NCo = 192 (3 column groups)
+    # 512 tiles or more: the streaming kernels deal them to the 8 XCDs in chunks
+    (9, 131, 224, 3, 64, 3, 3, 1, 16, True, True),  # 516 tiles, the last ragged; chunks of 2 (14 pixels per row)
+    (40, 1, 16000, 1, 64, 1, 9, 4, 32, False, False),  # Conv1d, 625 tiles, no rows to share
+    (2, 40, 448, 8, 64, 3, 3, 1, 1, True, False),   # F = 1 on aligned channels: 14 tiles per row, chunks of 64
 ]
 
 
