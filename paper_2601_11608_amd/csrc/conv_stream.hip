@@ -20,6 +20,7 @@
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <type_traits>
 
 #include "launch.h"
@@ -354,15 +355,16 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     // of the runtime once per instance), rounded so that the wave count is a
     // multiple of NG (each M tile is then finished by NG waves running side
     // by side) and no more tiles in flight than there are tiles.
-    static int resident = 0;  // workgroups per CU; benign race: every thread computes the same value
-    if (resident == 0) {
+    static std::atomic<int> resident{0};  // workgroups per CU; every thread that finds 0 computes the same value
+    int per_cu = resident.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
         int nb = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
                 &nb, conv_stream_kernel<TR, NT, KHM, KSM, OCC, true, false>, 256, 0) != hipSuccess || nb < 1)
             nb = OCC;
-        resident = nb > 2 ? 2 : nb;
+        per_cu = nb > 2 ? 2 : nb;
+        resident.store(per_cu, std::memory_order_relaxed);
     }
-    const int per_cu = resident;
     const unsigned parts = a.MT >= 64 * 8 ? 8 : 1;  // deal tiles per XCD unless there are too few tiles to split
     const unsigned waves = 256u * (unsigned)per_cu * 4u / parts;  // per XCD
     a.deal = fc_make_deal(a.MT, parts, waves / (unsigned)a.NG, g.KH, g.Wf_out);

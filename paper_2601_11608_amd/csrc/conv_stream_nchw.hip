@@ -17,6 +17,7 @@
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
 // w = F w' + f, applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <type_traits>
 
 #include "launch.h"
@@ -329,11 +330,11 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     const unsigned blocks = a.deal.J * 8;
     auto go = [&](auto kernel) {
         // more than 64 KB of dynamic LDS has to be allowed per kernel, once
-        static bool allowed = false;  // benign race: every thread sets the same attribute
-        if (!allowed) {
+        static std::atomic<bool> allowed{false};  // every thread that finds it false sets the same attribute
+        if (!allowed.load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 163840) != hipSuccess)
                 return (int)hipGetLastError();
-            allowed = true;
+            allowed.store(true, std::memory_order_release);
         }
         kernel<<<blocks, threads, lds_bytes, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
         return (int)hipGetLastError();
