@@ -239,3 +239,35 @@ def test_fold_factor_choice(fc):
         fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, F, "float16")
     lib = fc.load_library()
     assert lib.foldconv_choose_fold(1, 8, 8, 3, 4, 3, 3, 1, 1, None) == -1
+
+
+def _tiled_issued_flops(M, C, Co, F, KH, KW, pad, bn):
+    """MFMA flops of a band walk whose window is taken per `bn` output columns: for every tile the
+    16-wide K-steps between the first and last extended channel its output slots can touch, rounded
+    outwards to 8 (the plan's own accounting rule, restated here for the expected values below)."""
+    FC, NCo = F * C, F * Co
+    e_min, e_max = -((pad + F - 1) // F) * FC, ((F + KW - 2 - pad) // F + 1) * FC
+    total = 0.0
+    for n0 in range(0, NCo, bn):
+        n1 = min(n0 + bn, NCo)
+        g0, g1 = n0 // Co, (n1 - 1) // Co
+        lo = max(e_min, ((g0 - pad) * C) // 8 * 8)
+        hi = min(e_max, -(-((g1 + KW - pad) * C) // 8) * 8)
+        steps = -(-(hi - lo) // 16)
+        cols = -(-(n1 - n0) // 32) * 32
+        total += 2.0 * M * cols * steps * 16 * KH
+    return total
+
+
+def test_tile_width_of_the_tiled_kernel_follows_the_issued_work(fc):
+    """The 5-layer stack's MFMA-bound layers: 192-column tiles where they issue the least work
+    (F*C_out = 144 in one tile; 528 = 3 x 192 with 8 % padding), 128 for 272 columns, 256 for 1024."""
+    M = 32 * 112 * 28
+    for C, Co, bn in ((20, 36, 192), (36, 68, 128), (68, 132, 192), (132, 256, 256)):
+        s = fc.foldconv_plan(32, 112, 112, C, Co, 3, 3, 1, 4, "bfloat16").shapes
+        assert s.conv_kernel == 1  # tiled
+        want = _tiled_issued_flops(M, C, Co, 4, 3, 3, 1, bn)
+        assert abs(s.issued_flops_band - want) <= 1e-9 * want, (C, Co, bn, s.issued_flops_band, want)
+    # the two layers where the widths issue different amounts of work: the choice is the cheaper one by weight
+    assert _tiled_issued_flops(M, 68, 132, 4, 3, 3, 1, 192) < _tiled_issued_flops(M, 68, 132, 4, 3, 3, 1, 128)
+    assert _tiled_issued_flops(M, 36, 68, 4, 3, 3, 1, 128) < 0.93 * _tiled_issued_flops(M, 36, 68, 4, 3, 3, 1, 192)
