@@ -19,8 +19,11 @@ static long long floor_div_ll(long long a, long long b) {
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // MFMA flops issued by a kernel whose band window is taken per `tile_n`
-// output columns, in K-steps of `kstep` elements aligned to `align`.
-static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int align) {
+// output columns, in K-steps of `kstep` elements aligned to `align`.  The
+// LDS-tiled kernel walks K in blocks of 32 and multiplies whole tiles, the
+// columns past F*C_out included (full_tiles).
+static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int align, bool full_tiles = false) {
+    if (full_tiles) kstep = 32;
     g.band = band;
     double total = 0.0;
     for (int n0 = 0; n0 < g.NCo; n0 += tile_n) {
@@ -28,7 +31,7 @@ static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int alig
         int e_lo, e_hi;
         fc_band_window(g, n0, n1, align, &e_lo, &e_hi);
         long long steps = ((long long)(e_hi - e_lo) + kstep - 1) / kstep;
-        long long cols = ((n1 - n0) + 31) / 32 * 32;
+        long long cols = full_tiles ? tile_n : ((n1 - n0) + 31) / 32 * 32;
         total += 2.0 * (double)g.M * (double)cols * (double)(steps * kstep) * g.KH;
     }
     return total;
@@ -146,9 +149,10 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     ConvGeom g_dense = g, g_band = g, q_band = q;  // the tile width may depend on the walk
     g_dense.band = 0;
     g_band.band = q_band.band = 1;
-    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g_dense), kstep, fc_band_align(s.conv_kernel, dtype));
-    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g_band), kstep, fc_band_align(s.conv_kernel, dtype));
-    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q_band), kstep, fc_band_align(s.padded_kernel, dtype));
+    const bool ft = s.conv_kernel == FC_KERNEL_TILED, ftp = s.padded_kernel == FC_KERNEL_TILED;
+    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g_dense), kstep, fc_band_align(s.conv_kernel, dtype), ft);
+    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g_band), kstep, fc_band_align(s.conv_kernel, dtype), ft);
+    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q_band), kstep, fc_band_align(s.padded_kernel, dtype), ftp);
 
     *out = p;
     return FOLDCONV_OK;
@@ -209,11 +213,11 @@ extern "C" int foldconv_choose_fold(int N, int H, int W, int C_in, int C_out, in
         status = FOLDCONV_OK;
         const foldconv_shapes_t &s = p->s;
         const double bytes = (double)s.x_bytes + (double)s.y_bytes + (double)s.w_exp_bytes;
-        // sustained rates measured on MI355X with these kernels: 5.4 TB/s of the 8 TB/s HBM peak,
-        // 0.7 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
+        // sustained rates measured on MI355X with these kernels: 6.2 TB/s of the 8 TB/s HBM peak,
+        // 0.9 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
         // element-gather kernel that serves unaligned channel counts issues about 0.02 PFLOP/s
-        const double t_hbm = bytes / 5.4e12;
-        double rate = dtype == FOLDCONV_F32 ? 0.7e15 / 16.0 : 0.7e15;
+        const double t_hbm = bytes / 6.2e12;
+        double rate = dtype == FOLDCONV_F32 ? 0.9e15 / 16.0 : 0.9e15;
         if (s.conv_kernel == FC_KERNEL_GATHER) rate = 0.02e15;
         const double t_mfma = s.issued_flops_band / rate;
         const double t = t_hbm > t_mfma ? t_hbm : t_mfma;

@@ -230,8 +230,10 @@ def test_fold_factor_choice(fc):
     assert fc.foldconv_choose_fold(64, 224, 224, 3, 64, 3, 3, 1, "float16") == 8
     assert fc.foldconv_choose_fold(16, 1, 16000, 1, 64, 1, 9, 4, "float16") == 8
     assert fc.foldconv_choose_fold(32, 112, 112, 12, 48, 3, 3, 1, "bfloat16") == 2
-    # already aligned and MFMA-bound: folding only adds structural zeros
-    assert fc.foldconv_choose_fold(8, 56, 56, 64, 64, 3, 3, 1, "float16") == 1
+    # already aligned, but 64 output columns fill only half of the tiled kernel's 128-column tile: F = 2 fills it
+    # (measured at N = 64: 32 us against 39 us for F = 1); a layer that fills its tiles is left alone
+    assert fc.foldconv_choose_fold(8, 56, 56, 64, 64, 3, 3, 1, "float16") == 2
+    assert fc.foldconv_choose_fold(8, 56, 56, 64, 256, 3, 3, 1, "float16") == 1
     assert fc.foldconv_choose_fold(32, 112, 112, 132, 256, 3, 3, 1, "bfloat16") == 2     # 132 -> 264 = 33 * 8
     # width not divisible by 2: nothing to choose from
     assert fc.foldconv_choose_fold(1, 8, 9, 3, 4, 3, 3, 1, "float16") == 1
@@ -242,9 +244,10 @@ def test_fold_factor_choice(fc):
 
 
 def _tiled_issued_flops(M, C, Co, F, KH, KW, pad, bn):
-    """MFMA flops of a band walk whose window is taken per `bn` output columns: for every tile the
-    16-wide K-steps between the first and last extended channel its output slots can touch, rounded
-    outwards to 8 (the plan's own accounting rule, restated here for the expected values below)."""
+    """MFMA flops of the LDS-tiled kernel's band walk with `bn`-column tiles: for every tile the
+    32-wide K blocks between the first and last extended channel its output slots can touch
+    (rounded outwards to 8), times the whole tile width (the plan's own accounting rule, restated
+    here for the expected values below)."""
     FC, NCo = F * C, F * Co
     e_min, e_max = -((pad + F - 1) // F) * FC, ((F + KW - 2 - pad) // F + 1) * FC
     total = 0.0
@@ -253,9 +256,8 @@ def _tiled_issued_flops(M, C, Co, F, KH, KW, pad, bn):
         g0, g1 = n0 // Co, (n1 - 1) // Co
         lo = max(e_min, ((g0 - pad) * C) // 8 * 8)
         hi = min(e_max, -(-((g1 + KW - pad) * C) // 8) * 8)
-        steps = -(-(hi - lo) // 16)
-        cols = -(-(n1 - n0) // 32) * 32
-        total += 2.0 * M * cols * steps * 16 * KH
+        blocks = -(-(hi - lo) // 32)
+        total += 2.0 * M * bn * blocks * 32 * KH
     return total
 
 
