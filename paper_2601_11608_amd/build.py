@@ -15,6 +15,14 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function", "-fvisibility=hidden"]
 # Packed-fp32 VALU forms are disabled for all device code.
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-file device flags.  The dense-walk kernel keeps 216 registers of filter fragments per lane; it pins them
+# to the AGPR half of the register file and asks the compiler to put the MFMA results in VGPRs, where the
+# epilogue's VALU instructions read them directly (otherwise every finished tile costs 64 v_accvgpr_read).
+PER_FILE = {"conv_stream_lds.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
+def device_flags(src):
+    return DEVICE + PER_FILE.get(os.path.basename(src), [])
 
 
 def build(verbose=False):
@@ -27,7 +35,7 @@ def build(verbose=False):
     for s in srcs:
         o = os.path.join(objdir, os.path.basename(s) + ".o")
         objs.append(o)
-        cmd = [HIPCC] + COMMON + (DEVICE if s.endswith(".hip") else ["-x", "c++"]) + ["-c", s, "-o", o]
+        cmd = [HIPCC] + COMMON + (device_flags(s) if s.endswith(".hip") else ["-x", "c++"]) + ["-c", s, "-o", o]
         if s.endswith(".cpp"):
             cmd = ["g++"] + COMMON + ["-c", s, "-o", o]
         if verbose:

@@ -106,6 +106,13 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
             if (ci >= 0) v = wp[ci];  // structural zeros of the compact form
             wf[idx][nt] = __builtin_bit_cast(Vec, v);
         }
+    // Keep the resident filter in the AGPR half of the register file (the MFMAs read their A operand from
+    // there as well).  Built with the MFMA results in VGPRs (see the build script), the accumulators then
+    // sit where the epilogue's VALU instructions read them directly, and nothing is copied between the halves.
+#pragma unroll
+    for (int idx = 0; idx < S; ++idx)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) asm volatile("" : "+a"(wf[idx][nt]));
     // The bias is added in fp32 when a finished tile is rounded (one add per output value, issued
     // between MFMAs): on this walk the matrix pipeline is the bottleneck, so it is not spent on a
     // rank-1 bias product as in the band-walk kernel.

@@ -107,9 +107,11 @@ def compile_to_asm(src):
         pytest.skip("hipcc not available")
     with tempfile.TemporaryDirectory() as d:
         out = os.path.join(d, "k.s")
+        import sys
+        sys.path.insert(0, ROOT)
+        from paper_2601_11608_amd.build import device_flags   # the flags the library is built with
         subprocess.check_call(
-            [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-             "-packed-fp32-ops", "-S", "--cuda-device-only", src, "-o", out],
+            [HIPCC, "-O3", "-std=c++17"] + device_flags(src) + ["-S", "--cuda-device-only", src, "-o", out],
             stderr=subprocess.DEVNULL)
         return open(out).read()
 
@@ -293,6 +295,17 @@ def test_staged_input_kernel_waits(lds_asm):
         assert walk_lds_loads(lines, name, 7) > 10
         others = [l for l in lines if re.search(r"\bm0\b", l) and not l.startswith("s_mov_b32 m0,")]
         assert not others, (name, others[:3])        # M0 is written behind the compiler's back: nothing else may use it
+
+
+def test_staged_input_kernel_keeps_accumulators_where_the_epilogue_reads_them(lds_asm):
+    """Built with the library's flags, the filter fragments sit in AGPRs and the MFMA results in VGPRs:
+    the tile loop copies nothing between the two halves of the register file."""
+    for name in lds_kernel_names(lds_asm):
+        i = lds_asm.index(name + ":")
+        body = lds_asm[i:lds_asm.index(".Lfunc_end", i)]
+        loop = body[body.index("Loop Header"):]
+        assert "v_accvgpr" not in loop, name
+        assert re.search(r"v_mfma_f32_32x32x16_\w+ v\[\d+:\d+\], a\[\d+:\d+\], v\[", loop), name
 
 
 @pytest.mark.parametrize("mutation", ["weak_wait", "drop_store", "no_drain", "no_m0"])
