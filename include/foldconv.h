@@ -113,6 +113,9 @@ typedef struct foldconv_shapes_s {
     double issued_flops_dense;      /* MFMA flops issued with FOLDCONV_FLAG_DENSE_K           */
     double issued_flops_band;       /* MFMA flops issued by the default band walk             */
     double issued_flops_padded;     /* MFMA flops issued by conv_padded_forward               */
+    double model_seconds;           /* the fold-factor cost model's estimate of one
+                                       foldconv_forward (band walk, prepared filter); what
+                                       foldconv_choose_fold compares across fold factors      */
 } foldconv_shapes_t;
 
 /*

@@ -42,7 +42,7 @@ class Shapes(ctypes.Structure):
             "gemm_M", "gemm_N", "gemm_K", "x_bytes", "w_bytes", "bias_bytes", "w_exp_bytes", "y_bytes",
             "y_fold_bytes", "workspace_bytes", "padded_workspace_bytes", "filter_compact_bytes")]
         + [(n, ctypes.c_double) for n in (
-            "useful_flops", "issued_flops_dense", "issued_flops_band", "issued_flops_padded")]
+            "useful_flops", "issued_flops_dense", "issued_flops_band", "issued_flops_padded", "model_seconds")]
     )
 
     def as_dict(self):

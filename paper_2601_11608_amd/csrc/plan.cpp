@@ -21,8 +21,11 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // MFMA flops issued by a kernel whose band window is taken per `tile_n`
 // output columns, in K-steps of `kstep` elements aligned to `align`.  The
 // LDS-tiled kernel walks K in blocks of 32 and multiplies whole tiles, the
-// columns past F*C_out included (full_tiles).
-static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int align, bool full_tiles = false) {
+// columns past F*C_out included (full_tiles).  bias_k: K extent of the extra
+// rank-1 MFMA through which the vector kernels add the bias and initialise
+// their accumulators (one 16-wide step per 32 x 32 tile, issued whether or
+// not a bias is given; 0 for kernels that add the bias in fp32).
+static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int align, bool full_tiles, int bias_k) {
     if (full_tiles) kstep = 32;
     g.band = band;
     double total = 0.0;
@@ -32,9 +35,41 @@ static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int alig
         fc_band_window(g, n0, n1, align, &e_lo, &e_hi);
         long long steps = ((long long)(e_hi - e_lo) + kstep - 1) / kstep;
         long long cols = full_tiles ? tile_n : ((n1 - n0) + 31) / 32 * 32;
-        total += 2.0 * (double)g.M * (double)cols * (double)(steps * kstep) * g.KH;
+        total += 2.0 * (double)g.M * (double)cols * ((double)(steps * kstep) * g.KH + bias_k);
     }
     return total;
+}
+
+// MFMA flops a walk of geometry g issues on the kernel that serves it (the same routing as the
+// launch: a plan on the streaming kernel runs its dense walk on the LDS-staged variant where that
+// fits, else on the largest streaming instance, else on the tiled kernel).
+static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t dtype) {
+    g.band = band;
+    const int kstep = dtype == FOLDCONV_F32 ? 2 : 16;
+    const int align = fc_band_align(plan_kernel, dtype);
+    if (plan_kernel == FC_KERNEL_GATHER) return issued_flops(g, band, 32, kstep, align, false, 0);
+    if (plan_kernel == FC_KERNEL_STREAM) {
+        StreamShape sh;
+        if (!band && fc_stream_lds_ok(g)) return issued_flops(g, 0, 64, kstep, align, false, 0);  // bias added in fp32
+        if (fc_stream_shape(g, band, &sh)) return issued_flops(g, band, 32 * sh.nt, kstep, align, false, 16);
+    }
+    return issued_flops(g, band, fc_tiled_bn(g), kstep, align, true, 16);
+}
+
+// Fold-factor cost model (paper: the "lightweight cost model" of the MLIR section, in terms of
+// channel size, tile alignment and arithmetic intensity): estimated time of one band-walk
+// convolution = max(memory time, matrix time), each at the rate this library's kernels sustain
+// on MI355X for the kernel the plan routes to.
+static double model_seconds(const foldconv_shapes_t &s) {
+    const double bytes = (double)s.x_bytes + (double)s.y_bytes + (double)s.w_exp_bytes;
+    // sustained rates measured on MI355X with these kernels: 6.2 TB/s of the 8 TB/s HBM peak,
+    // 0.9 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
+    // element-gather kernel that serves unaligned channel counts issues about 0.02 PFLOP/s
+    const double t_hbm = bytes / 6.2e12;
+    double rate = s.dtype == FOLDCONV_F32 ? 0.9e15 / 16.0 : 0.9e15;
+    if (s.conv_kernel == FC_KERNEL_GATHER) rate = 0.02e15;
+    const double t_mfma = s.issued_flops_band / rate;
+    return t_hbm > t_mfma ? t_hbm : t_mfma;
 }
 
 extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
@@ -144,15 +179,10 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     p->ws_ypad = p->ws_bpad + align_up((size_t)Co_pad * eb, 256);
     s.padded_workspace_bytes = (long long)(p->ws_ypad + align_up((size_t)ypad_bytes, 256));
 
-    const bool mfma16 = dtype != FOLDCONV_F32;
-    const int kstep = mfma16 ? 16 : 2;
-    ConvGeom g_dense = g, g_band = g, q_band = q;  // the tile width may depend on the walk
-    g_dense.band = 0;
-    g_band.band = q_band.band = 1;
-    const bool ft = s.conv_kernel == FC_KERNEL_TILED, ftp = s.padded_kernel == FC_KERNEL_TILED;
-    s.issued_flops_dense = issued_flops(g, 0, fc_band_tile_n(s.conv_kernel, g_dense), kstep, fc_band_align(s.conv_kernel, dtype), ft);
-    s.issued_flops_band = issued_flops(g, 1, fc_band_tile_n(s.conv_kernel, g_band), kstep, fc_band_align(s.conv_kernel, dtype), ft);
-    s.issued_flops_padded = issued_flops(q, 1, fc_band_tile_n(s.padded_kernel, q_band), kstep, fc_band_align(s.padded_kernel, dtype), ftp);
+    s.issued_flops_dense = walk_flops(s.conv_kernel, g, 0, dtype);
+    s.issued_flops_band = walk_flops(s.conv_kernel, g, 1, dtype);
+    s.issued_flops_padded = walk_flops(s.padded_kernel, q, 1, dtype);
+    s.model_seconds = model_seconds(s);
 
     *out = p;
     return FOLDCONV_OK;
@@ -211,16 +241,7 @@ extern "C" int foldconv_choose_fold(int N, int H, int W, int C_in, int C_out, in
             continue;
         }
         status = FOLDCONV_OK;
-        const foldconv_shapes_t &s = p->s;
-        const double bytes = (double)s.x_bytes + (double)s.y_bytes + (double)s.w_exp_bytes;
-        // sustained rates measured on MI355X with these kernels: 6.2 TB/s of the 8 TB/s HBM peak,
-        // 0.9 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
-        // element-gather kernel that serves unaligned channel counts issues about 0.02 PFLOP/s
-        const double t_hbm = bytes / 6.2e12;
-        double rate = dtype == FOLDCONV_F32 ? 0.9e15 / 16.0 : 0.9e15;
-        if (s.conv_kernel == FC_KERNEL_GATHER) rate = 0.02e15;
-        const double t_mfma = s.issued_flops_band / rate;
-        const double t = t_hbm > t_mfma ? t_hbm : t_mfma;
+        const double t = p->s.model_seconds;
         if (best < 0.0 || t < best * (1.0 - 1e-9)) {
             best = t;
             *fold_factor = F;

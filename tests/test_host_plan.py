@@ -243,11 +243,20 @@ def test_fold_factor_choice(fc):
     assert lib.foldconv_choose_fold(1, 8, 8, 3, 4, 3, 3, 1, 1, None) == -1
 
 
+def test_model_estimate_is_reported_per_plan(fc):
+    """shapes.model_seconds is what foldconv_choose_fold compares: the pick has the smallest estimate."""
+    args = (64, 224, 224, 3, 64, 3, 3, 1)
+    pick = fc.foldconv_choose_fold(*args, "float16")
+    est = {F: fc.foldconv_plan(*args, F, "float16").shapes.model_seconds for F in (1, 2, 4, 8, 16, 32)}
+    assert all(v > 0 for v in est.values())
+    assert est[pick] == min(est.values())
+
+
 def _tiled_issued_flops(M, C, Co, F, KH, KW, pad, bn):
     """MFMA flops of the LDS-tiled kernel's band walk with `bn`-column tiles: for every tile the
     32-wide K blocks between the first and last extended channel its output slots can touch
-    (rounded outwards to 8), times the whole tile width (the plan's own accounting rule, restated
-    here for the expected values below)."""
+    (rounded outwards to 8), plus the one 16-wide step of the rank-1 bias product, times the whole
+    tile width (the plan's own accounting rule, restated here for the expected values below)."""
     FC, NCo = F * C, F * Co
     e_min, e_max = -((pad + F - 1) // F) * FC, ((F + KW - 2 - pad) // F + 1) * FC
     total = 0.0
@@ -257,7 +266,7 @@ def _tiled_issued_flops(M, C, Co, F, KH, KW, pad, bn):
         lo = max(e_min, ((g0 - pad) * C) // 8 * 8)
         hi = min(e_max, -(-((g1 + KW - pad) * C) // 8) * 8)
         blocks = -(-(hi - lo) // 32)
-        total += 2.0 * M * bn * blocks * 32 * KH
+        total += 2.0 * M * bn * (blocks * 32 * KH + 16)
     return total
 
 
