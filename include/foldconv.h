@@ -54,7 +54,9 @@ enum {
     FOLDCONV_ERR_INDIVISIBLE = -2, /* W % F != 0 (paper: guard at the top of Algorithm 1)     */
     FOLDCONV_ERR_UNSUPPORTED = -3, /* empty output, sizes beyond 32-bit tile indexing         */
     FOLDCONV_ERR_WORKSPACE = -4,   /* workspace missing, too small or not 256-byte aligned    */
-    FOLDCONV_ERR_HIP = -5          /* a HIP launch failed; hipGetLastError() was consumed     */
+    FOLDCONV_ERR_HIP = -5,         /* a HIP launch failed; hipGetLastError() was consumed     */
+    FOLDCONV_ERR_SCRATCH = -6      /* the problem needs more than FOLDCONV_STATIC_SCRATCH_BYTES
+                                      (foldconv_forward_static only)                          */
 };
 
 enum {
@@ -273,6 +275,29 @@ FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,
                      unsigned flags, void *stream);
+
+/*
+ * foldconv_forward for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same result, same kernels and same arguments as
+ * foldconv_forward, except that the kernel-order copy of w' is written to a
+ * device array inside the library (FOLDCONV_STATIC_SCRATCH_BYTES per GPU the
+ * library runs on, held until the process ends) instead of a caller
+ * workspace.  Nothing is allocated or freed, here or in anything it calls.
+ *   - plans with shapes.workspace_bytes above FOLDCONV_STATIC_SCRATCH_BYTES
+ *     return FOLDCONV_ERR_SCRATCH and launch nothing;
+ *   - every call re-packs w' (the scratch keeps whatever the last call on
+ *     this GPU wrote, for any plan), so FOLDCONV_FLAG_FILTER_PACKED and
+ *     FOLDCONV_FLAG_FILTER_COMPACT are FOLDCONV_ERR_BADARG here;
+ *   - all calls on one GPU share the one array: calls whose kernels may
+ *     overlap on that GPU (different streams, graphs replayed concurrently)
+ *     race; calls on one stream are ordered and safe;
+ *   - the first call on each GPU looks the array's device address up
+ *     (hipGetSymbolAddress); make that call outside stream capture.
+ */
+#define FOLDCONV_STATIC_SCRATCH_BYTES (16u << 20)
+FOLDCONV_API int foldconv_forward_static(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
+                                         const void *bias, void *y, unsigned flags, void *stream);
 
 /*
  * Reference path: zero-pad C_in up to shapes.C_pad in the input and the

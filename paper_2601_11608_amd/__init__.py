@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     FLAG_RELU,
     FOLD_H,
     FOLD_W,
+    STATIC_SCRATCH_BYTES,
     FoldconvError,
     Plan,
     conv_padded_forward,
@@ -20,6 +21,7 @@ from .binding import (  # noqa: F401
     foldconv_fold_input,
     foldconv_fold_input_nchw,
     foldconv_forward,
+    foldconv_forward_static,
     foldconv_pack_filter,
     foldconv_pack_filter_compact,
     foldconv_plan,

@@ -19,6 +19,7 @@ FLAG_FILTER_COMPACT = 16
 FLAG_OUT_NCHW = 32
 FOLD_W = 0
 FOLD_H = 1
+STATIC_SCRATCH_BYTES = 16 << 20
 
 _DTYPE_CODE = {"float32": 0, "float16": 1, "bfloat16": 2}
 
@@ -98,6 +99,8 @@ def load_library():
     lib.foldconv_pack_filter_compact.restype = ci
     lib.foldconv_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, ui, vp]
     lib.foldconv_forward.restype = ci
+    lib.foldconv_forward_static.argtypes = [vp, vp, vp, vp, vp, ui, vp]
+    lib.foldconv_forward_static.restype = ci
     lib.conv_padded_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, ui, vp]
     lib.conv_padded_forward.restype = ci
     lib.foldconv_strerror.argtypes = [ci]
@@ -288,6 +291,16 @@ def foldconv_forward(plan, x_fold, w_exp, bias, y, workspace=None, flags=0, stre
     _check(load_library().foldconv_forward(plan.handle, _ptr(x_fold), _ptr(w_exp), _ptr(bias), _ptr(y),
                                            _ptr(workspace), _nbytes(workspace), flags, _stream(stream)),
            "foldconv_forward")
+
+
+def foldconv_forward_static(plan, x_fold, w_exp, bias, y, flags=0, stream=None):
+    s = plan.shapes
+    _need(x_fold, s.x_bytes, "x_fold")
+    _need(w_exp, s.w_exp_bytes, "w_exp")
+    _need(bias, s.bias_bytes, "bias")
+    _need(y, s.y_fold_bytes if (flags & FLAG_KEEP_FOLDED) else s.y_bytes, "y")
+    _check(load_library().foldconv_forward_static(plan.handle, _ptr(x_fold), _ptr(w_exp), _ptr(bias), _ptr(y),
+                                                  flags, _stream(stream)), "foldconv_forward_static")
 
 
 def conv_padded_forward(plan, x, w, bias, y, workspace, flags=0, stream=None):

@@ -271,6 +271,7 @@ extern "C" const char *foldconv_strerror(int status) {
         case FOLDCONV_ERR_UNSUPPORTED: return "unsupported problem (empty output or size beyond kernel limits)";
         case FOLDCONV_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
         case FOLDCONV_ERR_HIP: return "HIP launch failed";
+        case FOLDCONV_ERR_SCRATCH: return "the problem needs more scratch than the library's static array holds";
         default: return "unknown status";
     }
 }

@@ -103,6 +103,39 @@ def test_plan_closed_forms_match_oracle(fc, oracle, N, H, W, C, Co, KH, KW, pad,
     p.destroy()
 
 
+def test_static_scratch_limit_is_checked_before_any_gpu_call(fc):
+    """foldconv_forward_static: a plan whose packed filter exceeds the library's static array is
+    refused with its own status (no GPU is needed to find that out), bad flags and plans likewise."""
+    lib = fc.load_library()
+    big = fc.foldconv_plan(1, 8, 64, 132, 256, 3, 3, 1, 16, "float16")
+    assert big.shapes.workspace_bytes > fc.STATIC_SCRATCH_BYTES
+    assert lib.foldconv_forward_static(big.handle, None, None, None, None, 0, None) == -6
+    assert "scratch" in fc.foldconv_strerror(-6)
+    ok = fc.foldconv_plan(1, 8, 64, 3, 64, 3, 3, 1, 16, "float16")
+    assert 0 < ok.shapes.workspace_bytes <= fc.STATIC_SCRATCH_BYTES
+    for flag in (fc.FLAG_FILTER_PACKED, fc.FLAG_FILTER_COMPACT):
+        assert lib.foldconv_forward_static(ok.handle, None, None, None, None, flag, None) == -1
+    assert lib.foldconv_forward_static(None, None, None, None, None, 0, None) == -1
+    header = open(HEADER).read()
+    assert int(re.search(r"FOLDCONV_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header).group(1)) << 20 == fc.STATIC_SCRATCH_BYTES
+
+
+def test_static_scratch_array_is_a_global_symbol_of_the_device_code():
+    """hipGetSymbolAddress finds a device variable by name in the code object: the static array behind
+    foldconv_forward_static must come out of the device compilation as a global, 256-byte aligned
+    object of the declared size (a local symbol makes the runtime's lookup fail at the first call)."""
+    src = os.path.join(ROOT, "paper_2601_11608_amd", "csrc", "static_scratch.hip")
+    with tempfile.TemporaryDirectory() as d:
+        asm = os.path.join(d, "s.s")
+        subprocess.check_call(["/opt/rocm/bin/hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "--cuda-device-only",
+                               "-S", src, "-o", asm], stderr=subprocess.DEVNULL)
+        text = open(asm).read()
+    assert re.search(r"\.globl\s+_ZL7scratch\b", text)
+    assert not re.search(r"\.local\s+_ZL7scratch\b", text)
+    assert re.search(r"\.size\s+_ZL7scratch, %d\b" % (16 << 20), text)
+    assert re.search(r"\.p2align\s+8", text)
+
+
 def test_headline_layer_numbers(fc):
     """Sizes of the 224x224 C_in = 3 first layer, F = 16."""
     s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
