@@ -53,7 +53,8 @@ enum {
     FOLDCONV_ERR_BADARG = -1,      /* null pointer, non-positive size, unknown dtype/flag     */
     FOLDCONV_ERR_INDIVISIBLE = -2, /* W % F != 0 (paper: guard at the top of Algorithm 1)     */
     FOLDCONV_ERR_UNSUPPORTED = -3, /* empty output, sizes beyond 32-bit tile indexing         */
-    FOLDCONV_ERR_WORKSPACE = -4,   /* workspace missing, too small or not 256-byte aligned    */
+    FOLDCONV_ERR_WORKSPACE = -4,   /* workspace missing, too small, not 256-byte aligned, or
+                                      claimed to hold a filter this plan never wrote there    */
     FOLDCONV_ERR_HIP = -5,         /* a HIP launch failed; hipGetLastError() was consumed     */
     FOLDCONV_ERR_SCRATCH = -6      /* the problem needs more than FOLDCONV_STATIC_SCRATCH_BYTES
                                       (foldconv_forward_static only)                          */
@@ -67,7 +68,9 @@ enum {
     FOLDCONV_FLAG_KEEP_FOLDED = 4u,   /* write y' [N][H_out][W'_out][F*C_out], not y           */
     FOLDCONV_FLAG_FILTER_PACKED = 8u, /* workspace already holds the packed filter written by a
                                          previous call with the same plan and the same filter
-                                         (weights are static after training): skip re-packing  */
+                                         (weights are static after training): skip re-packing.
+                                         The plan remembers the workspace it last packed into;
+                                         any other pointer is FOLDCONV_ERR_WORKSPACE           */
     FOLDCONV_FLAG_FILTER_COMPACT = 16u, /* workspace holds the compact filter written by
                                          foldconv_pack_filter_compact (only the non-zero blocks
                                          of w'); w_exp is not read and may be NULL              */
@@ -251,8 +254,8 @@ FOLDCONV_API int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, v
  * against the kernels' 8-row chunks (8/gcd(C_in,8) copies), built straight
  * from the ORIGINAL filter w [KH][KW][C_in][C_out] -- w' is never materialised.
  * Size: shapes.filter_compact_bytes (about KW/(KW'*F) of w').  Use the
- * workspace with foldconv_forward and FOLDCONV_FLAG_FILTER_COMPACT; results
- * are bit-identical to the packed-w' route.
+ * workspace with foldconv_forward (same plan) and FOLDCONV_FLAG_FILTER_COMPACT;
+ * results are bit-identical to the packed-w' route.
  * paper: section "Potential Optimizations for Sparsity and Quantization"
  * (store just the non-zero blocks of the block-structured filter).
  */
@@ -307,9 +310,10 @@ FOLDCONV_API int foldconv_forward_static(foldconv_plan_t plan, const void *x_fol
  * paper: the zero-padding alternative in the Introduction and in "Difference
  * from Channel Zero-Padding".  x and w are the ORIGINAL tensors; the padded
  * copies live in workspace (shapes.padded_workspace_bytes).  With
- * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again.
- * FOLDCONV_FLAG_KEEP_FOLDED, FOLDCONV_FLAG_DENSE_K,
- * FOLDCONV_FLAG_FILTER_COMPACT and FOLDCONV_FLAG_OUT_NCHW are ignored.
+ * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again (the workspace
+ * must be the one this plan's previous call prepared).  Flags other than
+ * FOLDCONV_FLAG_RELU and FOLDCONV_FLAG_FILTER_PACKED are FOLDCONV_ERR_BADARG:
+ * the reference path has no folded layout and no structural zeros to walk.
  */
 FOLDCONV_API int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias,
                         void *y, void *workspace, size_t workspace_bytes, unsigned flags,

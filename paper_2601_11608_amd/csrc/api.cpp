@@ -74,7 +74,9 @@ extern "C" int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, voi
     int st = check_ws(workspace, workspace_bytes, plan->s.workspace_bytes);
     if (st) return st;
     if (!aligned(w_exp, 2)) return FOLDCONV_ERR_BADARG;
-    return hip_status(fc_launch_pack(plan->fold, plan->s.elem_bytes, w_exp, workspace, stream));
+    st = hip_status(fc_launch_pack(plan->fold, plan->s.elem_bytes, w_exp, workspace, stream));
+    if (st == FOLDCONV_OK) fc_stamp(&plan->packed_ws, workspace);
+    return st;
 }
 
 extern "C" int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *w, void *workspace,
@@ -85,12 +87,20 @@ extern "C" int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *w,
     if (!aligned(w, (size_t)plan->s.elem_bytes)) return FOLDCONV_ERR_BADARG;
     // The gather kernel indexes the original filter itself: its compact form is a copy of w.
     if (plan->s.conv_kernel == FC_KERNEL_GATHER)
-        return hip_status(fc_launch_copy(w, workspace, (size_t)plan->s.w_bytes, stream));
-    return hip_status(fc_launch_compact(plan->fold, plan->s.elem_bytes, w, workspace, stream));
+        st = hip_status(fc_launch_copy(w, workspace, (size_t)plan->s.w_bytes, stream));
+    else
+        st = hip_status(fc_launch_compact(plan->fold, plan->s.elem_bytes, w, workspace, stream));
+    if (st == FOLDCONV_OK) fc_stamp(&plan->compact_ws, workspace);
+    return st;
 }
 
 extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, const void *bias,
                                 void *y, void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
+    return fc_forward(plan, x_fold, w_exp, bias, y, workspace, workspace_bytes, flags, stream, true);
+}
+
+int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, const void *bias, void *y, void *workspace,
+               size_t workspace_bytes, unsigned flags, void *stream, bool remember_workspace) {
     if (!plan_ok(plan) || !x_fold || !y) return FOLDCONV_ERR_BADARG;
     if (flags & ~kAllFlags) return FOLDCONV_ERR_BADARG;
     const bool compact = (flags & FOLDCONV_FLAG_FILTER_COMPACT) != 0;
@@ -117,6 +127,7 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
         // every kernel takes its filter operand from the workspace
         int st = check_ws(workspace, workspace_bytes, s.filter_compact_bytes);
         if (st) return st;
+        if (!fc_stamped(&plan->compact_ws, workspace)) return FOLDCONV_ERR_WORKSPACE;  // never packed by this plan
         if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
         g.compact = 1;
         if (out_nchw)
@@ -133,6 +144,9 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
         if (!(flags & FOLDCONV_FLAG_FILTER_PACKED)) {
             int e = fc_launch_pack(plan->fold, s.elem_bytes, w_exp, workspace, stream);
             if (e) return FOLDCONV_ERR_HIP;
+            if (remember_workspace) fc_stamp(&plan->packed_ws, workspace);
+        } else if (!fc_stamped(&plan->packed_ws, workspace)) {
+            return FOLDCONV_ERR_WORKSPACE;  // never packed by this plan
         }
     }
     if (out_nchw)
@@ -143,7 +157,8 @@ extern "C" int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const 
 extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias, void *y,
                                    void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
     if (!plan_ok(plan) || !x || !w || !y) return FOLDCONV_ERR_BADARG;
-    if (flags & ~kAllFlags) return FOLDCONV_ERR_BADARG;
+    // the reference path has one walk, one layout and one filter form
+    if (flags & ~(unsigned)(FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_FILTER_PACKED)) return FOLDCONV_ERR_BADARG;
     const foldconv_shapes_t &s = plan->s;
     const size_t eb = (size_t)s.elem_bytes;
     if (!aligned(x, eb) || !aligned(w, eb) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
@@ -157,6 +172,8 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
     const int kernel = s.padded_kernel;
     if (kernel != FC_KERNEL_GATHER && !pad_out && !aligned(y, 16)) return FOLDCONV_ERR_BADARG;
 
+    if ((flags & FOLDCONV_FLAG_FILTER_PACKED) && !fc_stamped(&plan->padded_ws, workspace))
+        return FOLDCONV_ERR_WORKSPACE;  // never prepared by this plan
     int e = fc_launch_pad_input(plan, x, x_pad, stream);
     if (e) return FOLDCONV_ERR_HIP;
     if (!(flags & FOLDCONV_FLAG_FILTER_PACKED)) {
@@ -166,6 +183,7 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
             e = fc_launch_pack(plan->padc, s.elem_bytes, w_pad, w_pack, stream);
             if (e) return FOLDCONV_ERR_HIP;
         }
+        fc_stamp(&plan->padded_ws, workspace);
     }
     if (pad_out && bias) {  // the bias is an argument of every call: pad it every time
         e = fc_launch_pad_bias(plan, bias, b_pad, stream);

@@ -20,7 +20,6 @@
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
-#include <atomic>
 #include <type_traits>
 
 #include "launch.h"
@@ -351,22 +350,14 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.MT = (unsigned)((g.M + 31) / 32);
     a.NG = (g.NCo + 32 * NT - 1) / (32 * NT);
     a.ksteps = ksteps;
-    // Persistent grid: as many workgroups as stay resident on 256 CUs (asked
-    // of the runtime once per instance), rounded so that the wave count is a
-    // multiple of NG (each M tile is then finished by NG waves running side
-    // by side) and no more tiles in flight than there are tiles.
-    static std::atomic<int> resident{0};  // workgroups per CU; every thread that finds 0 computes the same value
-    int per_cu = resident.load(std::memory_order_relaxed);
-    if (per_cu == 0) {
-        int nb = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
-                &nb, conv_stream_kernel<TR, NT, KHM, KSM, OCC, true, false>, 256, 0) != hipSuccess || nb < 1)
-            nb = OCC;
-        per_cu = nb > 2 ? 2 : nb;
-        resident.store(per_cu, std::memory_order_relaxed);
-    }
-    const unsigned parts = a.MT >= 64 * 8 ? 8 : 1;  // deal tiles per XCD unless there are too few tiles to split
-    const unsigned waves = 256u * (unsigned)per_cu * 4u / parts;  // per XCD
+    // Persistent grid: the workgroups the launch bounds keep resident on every compute unit, rounded
+    // so that the wave count is a multiple of NG (each M tile is then finished by NG waves running
+    // side by side) and no more tiles in flight than there are tiles.
+    FcDevice dev;
+    if (int e = fc_device(&dev)) return e;
+    const unsigned per_cu = (unsigned)OCC;
+    const unsigned parts = a.MT >= 64 * dev.xcds ? dev.xcds : 1;  // deal tiles per XCD unless there are too few tiles to split
+    const unsigned waves = dev.cus * per_cu * 4u / parts;  // per XCD
     a.deal = fc_make_deal(a.MT, parts, waves / (unsigned)a.NG, g.KH, g.Wf_out);
     const long long J = a.deal.J;
     const long long S = (long long)a.deal.stride * 32, plane = (long long)g.Hout * g.Wf_out;

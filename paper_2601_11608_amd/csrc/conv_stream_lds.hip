@@ -88,7 +88,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     const int cq = (int)(wgp % (unsigned)a.CQ);
     const unsigned j0 = wgp / (unsigned)a.CQ;
     if (j0 >= a.deal.J) return;  // workgroup-uniform
-    // Workgroup b runs on XCD b % 8; M tiles follow the workgroups in chunks (FcDeal).
+    // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).
     const unsigned t_first = fc_deal_first_tile(a.deal, part, j0);  // the workgroup's first tile
     const unsigned t_end = a.MT;
     const int n_lo = (cq * 4 + wave) * COLS;
@@ -203,16 +203,29 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
     unsigned d_m0 = 0;                   // ... of the finished tile
     int d_valid = 0;                             // 0: nothing finished yet, its stores are dropped
     __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, 0, 0x00020000);
-    auto epi_pack = [&](const floatx16_t (&done)[NT], int nt, int q) {
-        const float *bq = &bias_f[nt][4 * q];
-        u32x2 pk = {pack2l<TR>(done[nt][4 * q] + bq[0], done[nt][4 * q + 1] + bq[1]),
-                    pack2l<TR>(done[nt][4 * q + 2] + bq[2], done[nt][4 * q + 3] + bq[3])};
-        if (RELU) {
-            typedef short s16x4 __attribute__((ext_vector_type(4)));
-            const s16x4 z = {0, 0, 0, 0};
-            pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
+    // Accumulator element 4*q + j of lane (r, hf) is column 8*q + 4*hf + j of pixel r: a lane holds 8-byte
+    // pieces 16 bytes apart.  The two halves of the wave trade pieces (v_permlane32_swap: the upper 32
+    // lanes of the first operand against the lower 32 lanes of the second), after which lane (r, 0) holds
+    // columns 16*k .. 16*k+7 and lane (r, 1) columns 16*k+8 .. 16*k+15 of its pixel: one 16-byte LDS write
+    // per lane, free of bank conflicts at this row pitch (8-byte writes collide two ways).
+    auto epi_pack = [&](const floatx16_t (&done)[NT], int nt, int k) {
+        u32x2 pk[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int q = 2 * k + h;
+            const float *bq = &bias_f[nt][4 * q];
+            pk[h] = u32x2{pack2l<TR>(done[nt][4 * q] + bq[0], done[nt][4 * q + 1] + bq[1]),
+                          pack2l<TR>(done[nt][4 * q + 2] + bq[2], done[nt][4 * q + 3] + bq[3])};
+            if (RELU) {
+                typedef short s16x4 __attribute__((ext_vector_type(4)));
+                const s16x4 z = {0, 0, 0, 0};
+                pk[h] = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk[h]), z));
+            }
         }
-        *reinterpret_cast<u32x2 *>(slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * 2) = pk;
+        const u32x2 s0 = __builtin_amdgcn_permlane32_swap(pk[0][0], pk[1][0], false, false);
+        const u32x2 s1 = __builtin_amdgcn_permlane32_swap(pk[0][1], pk[1][1], false, false);
+        const u32x4 v = {s0[0], s1[0], s0[1], s1[1]};
+        *reinterpret_cast<u32x4 *>(slab + r * PITCH + (32 * nt + 16 * k + 8 * hf) * 2) = v;
     };
     auto epi_resource = [&]() {
         wave_lds_sync_l();
@@ -231,14 +244,14 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
         __builtin_amdgcn_raw_buffer_store_b128(st_val[p & 1], yr, st_lin[p], 0, 2 /* nt */);  // rows past the end of y fall outside the resource
         if (p == kStores - 1) wave_lds_sync_l();
     };
-    // piece number -> work: 8 pack-and-write pieces, the resource, the first read, 4 store(-and-read-next) pieces
+    // piece number -> work: 4 pack-and-write pieces, the resource, the first read, 4 store(-and-read-next) pieces
     auto epi_piece = [&](const floatx16_t (&done)[NT], int k) {
-        if (k < 8) epi_pack(done, k / 4, k % 4);
-        else if (k == 8) epi_resource();
-        else if (k == 9) epi_read(0);
-        else if (k < 10 + kStores) epi_store(k - 10);
+        if (k < 4) epi_pack(done, k / 2, k % 2);
+        else if (k == 4) epi_resource();
+        else if (k == 5) epi_read(0);
+        else if (k < 6 + kStores) epi_store(k - 6);
     };
-    constexpr int kPieces = 10 + kStores;
+    constexpr int kPieces = 6 + kStores;
     static_assert(S >= kPieces + 2 && S >= 4 * (NLW - 1) + 2, "the K loop is too short to hold the pieces");
 
     // Every tile's wait sees the same queue.  Each trip issues NLW loads (two tiles ahead) and
@@ -261,7 +274,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc_a[nt][i] = acc_b[nt][i] = 0.0f;
 #pragma unroll
-    for (int k = 8; k < kPieces; ++k) epi_piece(acc_a, k);  // stores dropped: d_valid = 0
+    for (int k = 4; k < kPieces; ++k) epi_piece(acc_a, k);  // stores dropped: d_valid = 0
 
     int cur_stage = 0;
     // one tile: accumulate into `acc` while the finished tile in `done` is rounded and stored
@@ -327,8 +340,10 @@ int launch_inst(const ConvGeom &g, const void *x, const void *wp, const void *bi
     LdsArgs a;
     a.MT = (unsigned)((g.M + 31) / 32);
     a.CQ = g.NCo / 256;
-    const unsigned parts = a.MT >= 64 * 8 ? 8 : 1;
-    a.deal = fc_make_deal(a.MT, parts, (256u / parts) / (unsigned)a.CQ, g.KH, g.Wf_out);  // one workgroup per compute unit
+    FcDevice dev;
+    if (int e = fc_device(&dev)) return e;
+    const unsigned parts = a.MT >= 64 * dev.xcds ? dev.xcds : 1;
+    a.deal = fc_make_deal(a.MT, parts, (dev.cus / parts) / (unsigned)a.CQ, g.KH, g.Wf_out);  // one workgroup per compute unit
     const long long J = a.deal.J;
     const long long S = (long long)a.deal.stride * 32, plane = (long long)g.Hout * g.Wf_out;
     const long long dI = S / plane;

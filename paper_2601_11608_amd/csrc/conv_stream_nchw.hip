@@ -153,8 +153,8 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     const int rd_off = sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;  // + k * C_out * 2 per slot
     const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;             // bytes per channel plane
 
-    // Workgroup b runs on XCD b % 8; M tiles follow the workgroups in chunks (FcDeal).
-    const unsigned xcd = blockIdx.x % 8u, wg = blockIdx.x / 8u;
+    // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).
+    const unsigned xcd = blockIdx.x % a.deal.parts, wg = blockIdx.x / a.deal.parts;
     const unsigned t_first = fc_deal_first_tile(a.deal, xcd, wg);  // the workgroup's first tile
 
     // first pixel of the workgroup's current tile, advanced incrementally
@@ -317,7 +317,9 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
     a.MT = (unsigned)((g.M + 31) / 32);
-    a.deal = fc_make_deal(a.MT, 8, 32u * per_cu, g.KH, g.Wf_out);
+    FcDevice dev;
+    if (int e = fc_device(&dev)) return e;
+    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu, g.KH, g.Wf_out);
     const long long S = 32LL * a.deal.stride, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
@@ -327,7 +329,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
-    const unsigned blocks = a.deal.J * 8;
+    const unsigned blocks = a.deal.J * a.deal.parts;
     auto go = [&](auto kernel) {
         // more than 64 KB of dynamic LDS has to be allowed per kernel, once
         static std::atomic<bool> allowed{false};  // every thread that finds it false sets the same attribute

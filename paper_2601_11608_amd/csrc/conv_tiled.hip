@@ -79,7 +79,8 @@ __device__ __forceinline__ unsigned pack2t<BF16Traits>(float a, float b) {
 struct TiledArgs {
     unsigned tiles_n, tiles_m;
     unsigned total;      // tiles_n * tiles_m
-    unsigned per_xcd;    // ceil(total / 8)
+    unsigned xcds;       // dies the workgroups are dealt to in turn
+    unsigned per_xcd;    // ceil(total / xcds)
     unsigned x_bytes, wp_bytes;
 };
 
@@ -96,10 +97,10 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
     constexpr int PLANE_F = L::PLANE_F, FILT = L::FILT, STAGE = L::STAGE, STAGES = L::STAGES, EPITCH = L::EPITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds[L::BYTES];
 
-    // Workgroup b runs on XCD b % 8.  Each XCD takes one contiguous range of tiles, N tiles
+    // Workgroup b runs on XCD b % xcds.  Each XCD takes one contiguous range of tiles, N tiles
     // fastest, so the tiles that share an input window meet in one L2.
-    const unsigned tile = (blockIdx.x % 8u) * a.per_xcd + blockIdx.x / 8u;
-    if (blockIdx.x / 8u >= a.per_xcd || tile >= a.total) return;  // uniform per workgroup
+    const unsigned tile = (blockIdx.x % a.xcds) * a.per_xcd + blockIdx.x / a.xcds;
+    if (blockIdx.x / a.xcds >= a.per_xcd || tile >= a.total) return;  // uniform per workgroup
     const unsigned tm = tile / a.tiles_n, tn = tile - tm * a.tiles_n;
     const int n0 = (int)tn * BN;
     const unsigned m0 = tm * BM;
@@ -382,11 +383,14 @@ int launch(const ConvGeom &g, const void *x, const void *wp, const void *bias, v
     const unsigned long long total = (unsigned long long)a.tiles_n * a.tiles_m;
     if (total > 0x7fffff00ull) return (int)hipErrorInvalidValue;
     a.total = (unsigned)total;
-    a.per_xcd = (a.total + 7) / 8;
+    FcDevice dev;
+    if (int e = fc_device(&dev)) return e;
+    a.xcds = dev.xcds;
+    a.per_xcd = (a.total + a.xcds - 1) / a.xcds;
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.wp_bytes = g.compact ? (unsigned)((long long)fc_compact_phases(g) * g.KH * g.cJ * g.Co * 16)
                            : (unsigned)((long long)g.KH * g.kwin * g.NCo * (long long)sizeof(T));
-    const unsigned blocks = a.per_xcd * 8;
+    const unsigned blocks = a.per_xcd * a.xcds;
     if (g.relu)
         conv_tiled_kernel<TR, TN, WM, true><<<blocks, THREADS, 0, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
     else

@@ -81,8 +81,8 @@ FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
 FC_HD int fc_gcd8(int c) { return (c % 8 == 0) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
 FC_HD int fc_compact_phases(const ConvGeom &g) { return 8 / g.cgcd; }
 
-// How the persistent streaming kernels deal their 32-pixel M tiles to the 8 XCDs (workgroup b runs
-// on XCD b % 8, each XCD has its own L2).  Tiles go out in chunks of CH consecutive tiles, chunk c
+// How the persistent streaming kernels deal their 32-pixel M tiles to the XCDs (8 on MI355X; workgroup
+// b runs on XCD b % parts, each XCD has its own L2).  Tiles go out in chunks of CH consecutive tiles, chunk c
 // to XCD c % parts: neighbouring tiles share their input rows inside one L2, and at any moment the
 // XCDs together write one compact region of y that moves through memory once (one contiguous range
 // of tiles per XCD instead means eight write fronts far apart, which the memory system serves
@@ -90,7 +90,7 @@ FC_HD int fc_compact_phases(const ConvGeom &g) { return 8 / g.cgcd; }
 // apart; slot j0 < J of XCD `part` starts at fc_deal_first_tile and then strides by parts*J tiles,
 // so every tile below MT is visited exactly once.
 struct FcDeal {
-    unsigned parts;   // 1 (too few tiles to split), or 8
+    unsigned parts;   // 1 (too few tiles to split), or the number of XCDs
     unsigned CH;      // tiles per chunk, divides J
     unsigned J;       // tiles in flight per XCD
     unsigned stride;  // parts * J
@@ -124,6 +124,22 @@ FC_HD unsigned fc_deal_first_tile(const FcDeal &d, unsigned part, unsigned j0) {
 
 enum { FC_KERNEL_GATHER = 0, FC_KERNEL_TILED = 1, FC_KERNEL_STREAM = 2 };
 
+struct FcStamps {
+    const void *ws[4];
+    unsigned next;
+};
+inline bool fc_stamped(const FcStamps *s, const void *ws) {
+    if (!ws) return false;
+    for (int i = 0; i < 4; ++i)
+        if (__atomic_load_n(&s->ws[i], __ATOMIC_RELAXED) == ws) return true;
+    return false;
+}
+inline void fc_stamp(FcStamps *s, const void *ws) {
+    if (fc_stamped(s, ws)) return;
+    const unsigned i = __atomic_fetch_add(&s->next, 1u, __ATOMIC_RELAXED) & 3u;
+    __atomic_store_n(&s->ws[i], ws, __ATOMIC_RELAXED);
+}
+
 struct foldconv_plan_s {
     uint32_t magic;
     foldconv_shapes_t s;
@@ -132,6 +148,12 @@ struct foldconv_plan_s {
     // byte offsets inside the padded-path workspace
     size_t ws_xpad, ws_wpad, ws_wpack, ws_bpad, ws_ypad;
     int fold_axis;  // FOLDCONV_FOLD_W, or FOLDCONV_FOLD_H for a channels-first plan built on the transposed image
+    // Where this plan wrote a kernel-order filter (foldconv_pack_filter, foldconv_forward without
+    // FOLDCONV_FLAG_FILTER_PACKED, foldconv_pack_filter_compact, conv_padded_forward): a later call that
+    // claims a prepared filter in a workspace the plan never wrote is refused instead of computing on
+    // garbage.  The last four workspaces of each kind are remembered (one plan may serve several streams,
+    // each with its own copy); relaxed atomics, plans may be shared between threads.
+    FcStamps packed_ws, compact_ws, padded_ws;
 };
 
 #define FOLDCONV_MAGIC 0xF01DC0DEu

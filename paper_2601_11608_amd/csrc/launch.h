@@ -22,6 +22,18 @@ struct StreamShape {
     X(4, 1, 2, 2) X(4, 3, 2, 2)
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 
+// --- the GPU the calling thread is on (device_info.hip); returns 0 or a hipError_t value ----------
+struct FcDevice {
+    unsigned cus;   // compute units
+    unsigned xcds;  // accelerator dies, each with its own L2; workgroup b is placed on die b % xcds
+};
+int fc_device(FcDevice *out);
+
+// --- foldconv_forward's body (api.cpp).  remember_workspace = false: the packed filter goes to a
+//     buffer the caller of the ABI never sees, so the plan does not record it as a prepared workspace.
+int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, const void *bias, void *y, void *workspace,
+               size_t workspace_bytes, unsigned flags, void *stream, bool remember_workspace);
+
 // --- launchers (return 0 or a hipError_t value) -------------------------------
 int fc_launch_expand(const foldconv_plan_s *p, const void *w, void *w_exp, int oihw, void *stream);
 int fc_launch_fold_nchw(const foldconv_plan_s *p, const void *x, void *x_fold, void *stream);

@@ -155,6 +155,14 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     q.cgcd = 8; q.cJ = KW * C_pad / 8;
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
+    if (W_out != Wf_out * F) {
+        // FOLDCONV_FLAG_KEEP_FOLDED stores rows of Wf_out*F*C_out elements instead of W_out*C_out: the
+        // kernel (and its 32-bit limits) must hold for both, the more general kernel wins
+        ConvGeom gk = g;
+        gk.out_row = (int)(Wf_out * FCo);
+        const int k2 = fc_choose_kernel(gk, dtype);
+        if (k2 < s.conv_kernel) s.conv_kernel = k2;
+    }
     s.padded_kernel = fc_choose_kernel(q, dtype);
     {
         ConvGeom gn = g;  // the streaming kernel's channels-first variant sees W_out as the stored row

@@ -5,7 +5,7 @@
 
 #include <mutex>
 
-#include "geom.h"
+#include "launch.h"
 
 // One copy per GPU the library runs on, resident until the process ends.  No kernel names the
 // array; it is kept, and made findable by name in the code object, because host code below takes
@@ -48,10 +48,10 @@ extern "C" int foldconv_forward_static(foldconv_plan_t plan, const void *x_fold,
     const long long need = plan->s.workspace_bytes;
     if (need > (long long)FOLDCONV_STATIC_SCRATCH_BYTES) return FOLDCONV_ERR_SCRATCH;
     if (need == 0)  // the element-gather kernel reads w' as it is: no scratch involved
-        return foldconv_forward(plan, x_fold, w_exp, bias, y, nullptr, 0, flags, stream);
+        return fc_forward(plan, x_fold, w_exp, bias, y, nullptr, 0, flags, stream, false);
     void *ptr = nullptr;
     const int st = scratch_on_current_device(&ptr);
     if (st != FOLDCONV_OK) return st;
     // same kernels as foldconv_forward: pack w' into the scratch, then the convolution reads it
-    return foldconv_forward(plan, x_fold, w_exp, bias, y, ptr, (size_t)FOLDCONV_STATIC_SCRATCH_BYTES, flags, stream);
+    return fc_forward(plan, x_fold, w_exp, bias, y, ptr, (size_t)FOLDCONV_STATIC_SCRATCH_BYTES, flags, stream, false);
 }

@@ -136,6 +136,22 @@ def test_static_scratch_array_is_a_global_symbol_of_the_device_code():
     assert re.search(r"\.p2align\s+8", text)
 
 
+def test_prepared_filter_flags_need_a_workspace_the_plan_wrote(fc):
+    """FILTER_PACKED / FILTER_COMPACT on a workspace this plan never packed into, and flags the zero-padded
+    reference path does not honour, are refused before anything is launched (pointers are never touched)."""
+    lib = fc.load_library()
+    p = fc.foldconv_plan(2, 8, 64, 3, 64, 3, 3, 1, 16, "float16")
+    s = p.shapes
+    fake = ctypes.c_void_p(0x7f0000000000)          # aligned, never dereferenced on the host
+    big = ctypes.c_size_t(1 << 30)
+    assert lib.foldconv_forward(p.handle, fake, fake, None, fake, fake, big, fc.FLAG_FILTER_PACKED, None) == -4
+    assert lib.foldconv_forward(p.handle, fake, None, None, fake, fake, big, fc.FLAG_FILTER_COMPACT, None) == -4
+    assert lib.conv_padded_forward(p.handle, fake, fake, None, fake, fake, big, fc.FLAG_FILTER_PACKED, None) == -4
+    for flag in (fc.FLAG_DENSE_K, fc.FLAG_KEEP_FOLDED, fc.FLAG_FILTER_COMPACT, fc.FLAG_OUT_NCHW, 1 << 20):
+        assert lib.conv_padded_forward(p.handle, fake, fake, None, fake, fake, big, flag, None) == -1, flag
+    assert s.workspace_bytes > 0
+
+
 def test_headline_layer_numbers(fc):
     """Sizes of the 224x224 C_in = 3 first layer, F = 16."""
     s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
