@@ -17,10 +17,10 @@
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
 // w = F w' + f, applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
-#include <atomic>
 #include <type_traits>
 
 #include "launch.h"
+#include "lds_attr.h"
 #include "mfma_types.h"
 
 namespace {
@@ -330,22 +330,19 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
     const unsigned blocks = a.deal.J * a.deal.parts;
-    auto go = [&](auto kernel) {
-        // more than 64 KB of dynamic LDS has to be allowed per kernel, once
-        static std::atomic<bool> allowed{false};  // every thread that finds it false sets the same attribute
-        if (!allowed.load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 163840) != hipSuccess)
-                return (int)hipGetLastError();
-            allowed.store(true, std::memory_order_release);
-        }
-        kernel<<<blocks, threads, lds_bytes, st>>>(g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);
-        return (int)hipGetLastError();
-    };
     const bool exact = g.KH == KHM && ksteps == KSM;
-    if (exact && g.relu) return go(conv_stream_nchw_kernel<TR, KHM, KSM, true, true>);
-    if (exact) return go(conv_stream_nchw_kernel<TR, KHM, KSM, true, false>);
-    if (g.relu) return go(conv_stream_nchw_kernel<TR, KHM, KSM, false, true>);
-    return go(conv_stream_nchw_kernel<TR, KHM, KSM, false, false>);
+#define FC_GO(EX, RL)                                                                                        \
+    do {                                                                                                     \
+        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL>>()) return e;            \
+        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL><<<blocks, threads, lds_bytes, st>>>(                   \
+            g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);                                 \
+    } while (0)
+    if (exact && g.relu) FC_GO(true, true);
+    else if (exact) FC_GO(true, false);
+    else if (g.relu) FC_GO(false, true);
+    else FC_GO(false, false);
+#undef FC_GO
+    return (int)hipGetLastError();
 }
 
 template <typename TR>
