@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 KERNEL_NAMES = ["gather", "tiled", "stream"]
 EXTRAS = ["dense_k", "padded", "repack", "compact_filter", "copies", "c5_stack", "small_configs", "gemm_1x1", "nchw",
-          "fold_choice"]
+          "fold_choice", "operand_values"]
 
 
 def measured_traffic_bytes():
@@ -160,7 +160,7 @@ def fold_choice_table(fc, runner, wl, torch):
             nb = rotating_sets(s.x_bytes + s.y_bytes, hi=12)
             xs = [x.cuda() for _ in range(nb)]
             ys = [L.new_output() for _ in range(nb)]
-            fns = [(lambda xi=xi, yi=yi: L.forward(xi, yi)) for xi, yi in zip(xs, ys)]
+            fns = [(lambda xi=xi, yi=yi: L.forward(xi, yi, compact=None)) for xi, yi in zip(xs, ys)]
             row["measured_us"][str(F)] = graph_us_per_launch(fns, min_launches=nb, replays=6, warmup=2)
             del L, xs, ys, fns
             F *= 2
@@ -327,24 +327,29 @@ def main():
         stack = runner.FoldedStack(l5, w5, b5)
         x5d = x5.cuda()
         flops5 = sum(L5.plan.shapes.useful_flops for L5 in stack.layers)
-        _, s_ms = time_events(lambda: stack.forward(x5d), 20, 15)  # long warm-up: the first launches after idling run slower
-        _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 20, 5)
+        # the stack as a user would run it: every layer from the filter form its plan prefers (packed w' for
+        # the small layers, the compact form for the two large ones); then all-packed and all-compact
+        # (long warm-up first: the launches after the GPU has idled run slower, whichever variant they are)
+        _, spk_ms = time_events(lambda: stack.forward(x5d, compact=False), 20, 15)
         _, sc_ms = time_events(lambda: stack.forward(x5d, compact=True), 20, 5)
+        _, s_ms = time_events(lambda: stack.forward(x5d, compact=None), 20, 5)
+        _, sp_ms = time_events(lambda: stack.forward(x5d, padded=True), 20, 5)
         # each layer on its own (events around 20 launches, input = the previous layer's output)
         per_layer = []
         a = x5d
         for L5, y5 in zip(stack.layers, stack.outs):
-            _, l_ms = time_events(lambda: L5.forward(a, y5), 20, 3)
+            _, l_ms = time_events(lambda: L5.forward(a, y5, compact=None), 20, 3)
             s5 = L5.plan.shapes
             per_layer.append({"ms": l_ms, "F": s5.F, "kernel": KERNEL_NAMES[s5.conv_kernel],
+                              "filter": "compact" if s5.prefer_compact else "packed",
                               "useful_tflops": s5.useful_flops / (l_ms * 1e-3) / 1e12,
                               "issued_tflops": s5.issued_flops_band / (l_ms * 1e-3) / 1e12,
                               "issued_over_useful": s5.issued_flops_band / s5.useful_flops})
             a = y5
         # the same five launches replayed from a captured HIP graph (no per-launch host work)
-        sg_ms = graph_us_per_launch([lambda: stack.forward(x5d, compact=True)], min_launches=1, replays=20, warmup=5) * 1e-3
-        extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "folded_compact_filter_ms": sc_ms,
-                              "folded_compact_filter_graph_ms": sg_ms,
+        sg_ms = graph_us_per_launch([lambda: stack.forward(x5d, compact=None)], min_launches=1, replays=20, warmup=5) * 1e-3
+        extras["c5_stack"] = {"folded_ms": s_ms, "padded_ms": sp_ms, "folded_packed_filter_ms": spk_ms,
+                              "folded_compact_filter_ms": sc_ms, "folded_graph_ms": sg_ms,
                               "per_layer": per_layer,
                               "filter_bytes": {"expanded": sum(int(L5.plan.shapes.w_exp_bytes) for L5 in stack.layers),
                                                "compact": sum(int(L5.plan.shapes.filter_compact_bytes) for L5 in stack.layers)},
@@ -352,6 +357,24 @@ def main():
                               "useful_pct_of_mfma_peak": 100.0 * flops5 / (s_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                               "kernels": [KERNEL_NAMES[L5.plan.shapes.conv_kernel] for L5 in stack.layers]}
         del stack, x5d
+    if "operand_values" in want:
+        # The MFMA-bound layer of the stack (132 -> 256 channels) with its seeded operands and with all-zero
+        # operands: same kernel, same launch, same memory traffic; what differs is the clock the power
+        # management allows (profiles/conv_tiled_c5_bf16.md reads the cycle counters of these launches).
+        l5 = wl.CONFIGS["c5"][4]
+        x5, w5, b5 = wl.make_layer(l5, 4005)
+        ov = {}
+        for name, xv, wv in (("seeded", x5, w5), ("zero", torch.zeros_like(x5), torch.zeros_like(w5))):
+            Lv = runner.FoldedLayer(l5, wv, b5)
+            xvd = xv.cuda()
+            yv = Lv.new_output()
+            _, v_ms = time_events(lambda: Lv.forward(xvd, yv, compact=None), 40, 10)
+            sv = Lv.plan.shapes
+            ov[name] = {"kernel_ms": v_ms, "issued_tflops": sv.issued_flops_band / (v_ms * 1e-3) / 1e12,
+                        "issued_pct_of_mfma_peak": 100.0 * sv.issued_flops_band / (v_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+            del Lv, xvd, yv
+        ov["note"] = "c5 layer 5 alone, 40 launches back to back after 10 warm-ups, per operand values"
+        extras["operand_values"] = ov
     if "small_configs" in want:
         # the small configurations (parity-test cases, not the headline) and the first layer of the stack:
         # launches replayed from a captured graph (so that the per-launch host work of the Python binding

@@ -108,6 +108,10 @@ typedef struct foldconv_shapes_s {
                                        width-folded 16-bit plan on the streaming kernel, F a
                                        multiple of 8, F*C_out a multiple of 64 and at most 1024,
                                        W_out == F*W_out_fold, y below 4 GiB                     */
+    int32_t prefer_compact;         /* hint: 1 when foldconv_forward is expected to run faster from
+                                       the compact filter than from packed w' (large-K layers whose
+                                       packed band would crowd the input out of the L2: measured
+                                       10-13 % on the 68 -> 132 and 132 -> 256 layers), else 0   */
     int64_t gemm_M, gemm_N, gemm_K; /* implicit GEMM of the folded problem, dense K           */
     int64_t x_bytes, w_bytes, bias_bytes, w_exp_bytes, y_bytes, y_fold_bytes;
     int64_t workspace_bytes;        /* for foldconv_forward / foldconv_pack_filter            */

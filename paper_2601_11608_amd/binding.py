@@ -38,7 +38,7 @@ class Shapes(ctypes.Structure):
             "N", "H", "W", "C_in", "C_out", "KH", "KW", "pad", "F", "dtype", "pad_h", "pad_w",
             "W_fold", "C_fold", "Co_fold", "d_min", "d_max", "KW_fold", "pad_left_fold", "pad_right_fold",
             "H_out", "W_out", "W_out_fold", "unfold_is_alias", "C_pad", "C_out_pad", "elem_bytes", "conv_kernel",
-            "padded_kernel", "fold_axis", "out_nchw_fused")]
+            "padded_kernel", "fold_axis", "out_nchw_fused", "prefer_compact")]
         + [(n, ctypes.c_int64) for n in (
             "gemm_M", "gemm_N", "gemm_K", "x_bytes", "w_bytes", "bias_bytes", "w_exp_bytes", "y_bytes",
             "y_fold_bytes", "workspace_bytes", "padded_workspace_bytes", "filter_compact_bytes")]

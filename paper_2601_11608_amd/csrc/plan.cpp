@@ -58,18 +58,40 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 
 // Fold-factor cost model (paper: the "lightweight cost model" of the MLIR section, in terms of
 // channel size, tile alignment and arithmetic intensity): estimated time of one band-walk
-// convolution = max(memory time, matrix time), each at the rate this library's kernels sustain
-// on MI355X for the kernel the plan routes to.
-static double model_seconds(const foldconv_shapes_t &s) {
-    const double bytes = (double)s.x_bytes + (double)s.y_bytes + (double)s.w_exp_bytes;
-    // sustained rates measured on MI355X with these kernels: 6.2 TB/s of the 8 TB/s HBM peak,
-    // 0.9 PFLOP/s issued of the 2.5 PFLOP/s 16-bit MFMA peak (fp32 MFMA: 1/16 of that); the
-    // element-gather kernel that serves unaligned channel counts issues about 0.02 PFLOP/s
-    const double t_hbm = bytes / 6.2e12;
-    double rate = s.dtype == FOLDCONV_F32 ? 0.9e15 / 16.0 : 0.9e15;
-    if (s.conv_kernel == FC_KERNEL_GATHER) rate = 0.02e15;
-    const double t_mfma = s.issued_flops_band / rate;
-    return t_hbm > t_mfma ? t_hbm : t_mfma;
+// convolution on the kernel the plan routes to,
+//     launch-and-drain overhead + max(memory time, matrix time) + filter term,
+// with the rates these kernels sustain on MI355X (fitted to the timings of every legal power-of-two
+// fold factor of the benchmark layers, rotating buffers, graph replay):
+//   * memory: x + y + filter bytes at 6.2 TB/s (of the 8 TB/s HBM peak).  On the streaming kernel a wave
+//     owns 64 (or 128) output columns, so y counts at F*C_out rounded up to whole waves: idle
+//     lanes store nothing but take their turn (tile alignment);
+//   * matrix: issued MFMA flops (band walk, tile padding and the rank-1 bias product included) at
+//     1.0 PFLOP/s on the streaming kernel and 0.85 PFLOP/s on the tiled kernel (of the 2.5 PFLOP/s
+//     16-bit peak; what the clock management leaves to real operands), 0.05 PFLOP/s on the
+//     element-gather kernel that serves fp32 and channel counts off the 16-byte chunk alignment;
+//   * filter term: the expanded filter read at 1 TB/s (every wave fetches its own fragments; a larger
+//     F buys nothing once F*C_in is aligned, and its F^2 larger filter is not free);
+//   * overhead: 4.5 us (streaming), 8 us (tiled), 10 us (gather) per launch.
+static double model_seconds(const foldconv_shapes_t &s, int wave_columns) {
+    const double x = (double)s.x_bytes, y = (double)s.y_bytes;
+    const double wf = s.prefer_compact ? (double)s.filter_compact_bytes : (double)s.w_exp_bytes;
+    const double hbm = 6.2e12;
+    double overhead, rate, y_eff = y;
+    if (s.conv_kernel == FC_KERNEL_STREAM) {
+        overhead = 4.5e-6;
+        rate = 1.0e15;
+        const double cols = (double)((s.Co_fold + wave_columns - 1) / wave_columns) * wave_columns;
+        y_eff = y * cols / (double)s.Co_fold;
+    } else if (s.conv_kernel == FC_KERNEL_TILED) {
+        overhead = 8e-6;
+        rate = 0.85e15;
+    } else {
+        overhead = 10e-6;
+        rate = s.dtype == FOLDCONV_F32 ? 0.012e15 : 0.05e15;
+    }
+    const double t_mem = (x + y_eff + wf) / hbm;
+    const double t_mma = s.issued_flops_band / rate;
+    return overhead + (t_mem > t_mma ? t_mem : t_mma) + wf / 1e12;
 }
 
 extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, int KW, int pad,
@@ -187,10 +209,15 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     p->ws_ypad = p->ws_bpad + align_up((size_t)Co_pad * eb, 256);
     s.padded_workspace_bytes = (long long)(p->ws_ypad + align_up((size_t)ypad_bytes, 256));
 
+    // Both filter forms run the same instructions; what differs is the L2 footprint.  On the tiled
+    // kernel a packed band of a few megabytes competes with the input rows for the 4 MB L2 of an
+    // XCD, and the compact form (one tap matrix for all slots) measured 10-13 % faster there;
+    // below that the packed form wins by as much (its staging loads are always contiguous).
+    s.prefer_compact = (s.conv_kernel == FC_KERNEL_TILED && s.w_exp_bytes >= (2LL << 20)) ? 1 : 0;
     s.issued_flops_dense = walk_flops(s.conv_kernel, g, 0, dtype);
     s.issued_flops_band = walk_flops(s.conv_kernel, g, 1, dtype);
     s.issued_flops_padded = walk_flops(s.padded_kernel, q, 1, dtype);
-    s.model_seconds = model_seconds(s);
+    s.model_seconds = model_seconds(s, fc_band_tile_n(s.conv_kernel, g));
 
     *out = p;
     return FOLDCONV_OK;

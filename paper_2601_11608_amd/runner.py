@@ -33,7 +33,10 @@ class FoldedLayer:
 
     def forward(self, x, y, flags=0, repack=False, compact=False):
         """fold (aliased: x' shares x's bytes) + folded convolution + fused reconstruct.
-        compact=True runs from the compact filter (non-zero blocks only), built once from w."""
+        compact=True runs from the compact filter (non-zero blocks only), built once from w;
+        compact=None takes the plan's hint (shapes.prefer_compact)."""
+        if compact is None:
+            compact = bool(self.plan.shapes.prefer_compact)
         fc.foldconv_fold_input(self.plan, x, x)
         if self.layer.relu:
             flags |= fc.FLAG_RELU
@@ -69,6 +72,7 @@ class FoldedStack:
         self.outs = [l.new_output() for l in self.layers]
 
     def forward(self, x, flags=0, padded=False, compact=False):
+        """compact: False = packed w' everywhere, True = compact filter everywhere, None = per layer as the plan hints."""
         a = x
         for l, y in zip(self.layers, self.outs):
             if padded:

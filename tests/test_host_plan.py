@@ -275,21 +275,41 @@ def test_gemm_plan_is_a_folded_one_by_one_conv(fc):
 
 def test_fold_factor_choice(fc):
     """Cost model: fold small misaligned C_in up to the chunk alignment, leave aligned wide layers alone."""
-    # C_in = 3: no factor below 8 makes F*C_in a multiple of 8
+    # C_in = 3 or 1: no factor below 8 makes F*C_in a multiple of 8; a larger F only grows the filter
     assert fc.foldconv_choose_fold(64, 224, 224, 3, 64, 3, 3, 1, "float16") == 8
     assert fc.foldconv_choose_fold(16, 1, 16000, 1, 64, 1, 9, 4, "float16") == 8
-    assert fc.foldconv_choose_fold(32, 112, 112, 12, 48, 3, 3, 1, "bfloat16") == 2
-    # already aligned, but 64 output columns fill only half of the tiled kernel's 128-column tile: F = 2 fills it
-    # (measured at N = 64: 32 us against 39 us for F = 1); a layer that fills its tiles is left alone
-    assert fc.foldconv_choose_fold(8, 56, 56, 64, 64, 3, 3, 1, "float16") == 2
+    # C_in = 12: aligned from F = 2 on, but F*C_out = 96 fills only one and a half 64-column waves; F = 4 fills three
+    assert fc.foldconv_choose_fold(32, 112, 112, 12, 48, 3, 3, 1, "bfloat16") == 4
+    # a layer that is aligned and fills its tiles is left alone
     assert fc.foldconv_choose_fold(8, 56, 56, 64, 256, 3, 3, 1, "float16") == 1
-    assert fc.foldconv_choose_fold(32, 112, 112, 132, 256, 3, 3, 1, "bfloat16") == 2     # 132 -> 264 = 33 * 8
     # width not divisible by 2: nothing to choose from
     assert fc.foldconv_choose_fold(1, 8, 9, 3, 4, 3, 3, 1, "float16") == 1
     for F in (8, 16):                      # every choice must be a legal plan
         fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, F, "float16")
     lib = fc.load_library()
     assert lib.foldconv_choose_fold(1, 8, 8, 3, 4, 3, 3, 1, 1, None) == -1
+
+
+def test_fold_factor_choice_against_the_measured_table(fc):
+    """tests/golden/fold_choice_measured.json holds the times bench.py measured on an MI355X for every legal
+    power-of-two fold factor of the benchmark layers.  The model's pick must be within 5 % of the fastest
+    measured factor on every layer, and its estimate within 45 % of the measurement for every factor that
+    runs a vector kernel (the model's constants were fitted to this table)."""
+    import json
+
+    table = json.load(open(os.path.join(ROOT, "tests", "golden", "fold_choice_measured.json")))["layers"]
+    assert len(table) == 8
+    for name, row in table.items():
+        meas = {int(F): t for F, t in row["measured_us"].items() if t is not None}
+        pick = fc.foldconv_choose_fold(*row["args"], row["dtype"])
+        assert pick in meas, (name, pick)
+        best = min(meas.values())
+        assert meas[pick] <= 1.05 * best, (name, pick, meas)
+        for F, t in meas.items():
+            args = row["args"]
+            s = fc.foldconv_plan(*args, F, row["dtype"]).shapes
+            if s.conv_kernel != 0:
+                assert abs(s.model_seconds * 1e6 - t) <= 0.45 * t, (name, F, s.model_seconds * 1e6, t)
 
 
 def test_model_estimate_is_reported_per_plan(fc):
