@@ -74,9 +74,10 @@ enum {
     FOLDCONV_FLAG_FILTER_COMPACT = 16u, /* workspace holds the compact filter written by
                                          foldconv_pack_filter_compact (only the non-zero blocks
                                          of w'); w_exp is not read and may be NULL              */
-    FOLDCONV_FLAG_OUT_NCHW = 32u      /* write y channels-first, [N][C_out][H_out][W_out], in the
-                                         same launch (no y' round trip through memory).  Only
-                                         where shapes.out_nchw_fused is 1, else
+    FOLDCONV_FLAG_OUT_NCHW = 32u      /* write y channels-first, [N][C_out][H_out][W_out] of the
+                                         image, in the same launch (no y' round trip through
+                                         memory), for width- and height-folded plans.  Only where
+                                         shapes.out_nchw_fused is 1, else
                                          FOLDCONV_ERR_UNSUPPORTED; excludes KEEP_FOLDED          */
 };
 
@@ -105,9 +106,10 @@ typedef struct foldconv_shapes_s {
                                        foldconv_plan_nchw with height folding: then H, W, KH, KW
                                        and the *_out fields above describe the transposed image */
     int32_t out_nchw_fused;         /* 1 when foldconv_forward accepts FOLDCONV_FLAG_OUT_NCHW:
-                                       width-folded 16-bit plan on the streaming kernel, F a
-                                       multiple of 8, F*C_out a multiple of 64 and at most 1024,
-                                       W_out == F*W_out_fold, y below 4 GiB                     */
+                                       16-bit plan on the streaming kernel, F*C_out a multiple of
+                                       64 and at most 1024, C_out a multiple of 4, y below 4 GiB;
+                                       width fold: F a multiple of 8 and W_out == F*W_out_fold;
+                                       height fold: the image's W_out a multiple of 8           */
     int32_t prefer_compact;         /* hint: 1 when foldconv_forward is expected to run faster from
                                        the compact filter than from packed w' (large-K layers whose
                                        packed band would crowd the input out of the L2: measured
@@ -277,7 +279,8 @@ FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *
  * may be NULL when that is 0; with FOLDCONV_FLAG_FILTER_COMPACT it is the
  * compact filter (shapes.filter_compact_bytes) and w_exp is ignored.
  * With FOLDCONV_FLAG_OUT_NCHW the reconstructed output is written
- * channels-first, y[n][co][h][F*w'+g] (shapes.y_bytes, 16-byte aligned).
+ * channels-first, y[n][co][h][F*w'+g] for a width fold and
+ * y[n][co][F*h'+g][w] for a height fold (shapes.y_bytes, 16-byte aligned).
  */
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,

@@ -117,11 +117,12 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
 
     int kernel = s.conv_kernel;
     const bool out_nchw = (flags & FOLDCONV_FLAG_OUT_NCHW) != 0;
+    const bool hfold = plan->fold_axis == FOLDCONV_FOLD_H;
     if (out_nchw) {
         if (flags & FOLDCONV_FLAG_KEEP_FOLDED) return FOLDCONV_ERR_BADARG;
         g.out_row = s.W_out;
         int ks = 0;
-        if (!s.out_nchw_fused || !fc_stream_nchw_ok(g, g.band, &ks)) return FOLDCONV_ERR_UNSUPPORTED;
+        if (!s.out_nchw_fused || !fc_stream_nchw_ok(g, g.band, hfold, &ks)) return FOLDCONV_ERR_UNSUPPORTED;
     }
     if (compact) {
         // every kernel takes its filter operand from the workspace
@@ -131,7 +132,7 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
         if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
         g.compact = 1;
         if (out_nchw)
-            return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, x_fold, workspace, bias, y, stream));
+            return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, x_fold, workspace, bias, y, stream));
         return hip_status(
             fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, workspace, workspace, bias, y, stream));
     }
@@ -150,7 +151,7 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
         }
     }
     if (out_nchw)
-        return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, x_fold, workspace, bias, y, stream));
+        return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, x_fold, workspace, bias, y, stream));
     return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, w_exp, workspace, bias, y, stream));
 }
 

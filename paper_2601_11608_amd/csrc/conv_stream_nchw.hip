@@ -14,8 +14,16 @@
 // 16-bit values in registers into four 16-byte pieces, one per channel, each
 // holding 8 consecutive image columns; a wave's store instruction covers a
 // contiguous run of 64 such pieces of one channel row.
+//
+// Height-folded plans (HF: the plan describes the transposed image, its rows are image
+// columns and its folded axis is the image height) take the same route with another tile
+// shape.  There the contiguous axis of y, w, runs across plan rows, so an M tile is 32
+// consecutive plan rows at one folded column b' (instead of 32 consecutive folded pixels of a
+// row), and a thread of the write-out reads the same four channels of one slot from eight
+// neighbouring pixels: again four 16-byte pieces of 8 consecutive image columns, now at image
+// row h = F*b' + g.
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
-// w = F w' + f, applied on the way to a channels-first tensor.
+// w = F w' + f (h = F h' + f for a height fold), applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
@@ -54,6 +62,7 @@ struct NchwArgs {
     int ksteps;           // 16-wide K-steps per kh actually walked (<= KSM)
     int pitch;            // bytes per pixel row of the assembled tile
     int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
+    unsigned tiles_ab;    // HF: tiles per folded column, ceil(Hout / 32)
 };
 
 template <int I, int N, class F>
@@ -70,7 +79,7 @@ __device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigne
 }
 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
-template <typename TR, int KHM, int KSM, bool EXACT, bool RELU>
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF>
 __global__ void __launch_bounds__(1024, 1)
 conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                         const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
@@ -145,28 +154,56 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
     // ---- this thread's share of the write-out: pixel sp of the tile, slots [8*sg8, 8*sg8+8),
     //      channels [4*co4, 4*co4+4): 32 * (F/8) threads per channel quadruple, C_out/4 quadruples
-    const int g8n = g.F >> 3;
+    //      (HF: pixels [8*da8, 8*da8+8) of the tile, slot hg, channels [4*co4, 4*co4+4): C_out/4 threads per
+    //      (slot, pixel group), consecutive lanes on consecutive channel quadruples)
+    const int g8n = HF ? 1 : g.F >> 3;
     const int per_c4 = 32 * g8n;
-    const int co4 = t / per_c4;
-    const int sp = (t - co4 * per_c4) / g8n;
-    const int sg8 = (t - co4 * per_c4) - sp * g8n;
-    const int rd_off = sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;  // + k * C_out * 2 per slot
-    const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;             // bytes per channel plane
+    const int c4n = g.Co >> 2;
+    const int co4 = HF ? t % c4n : t / per_c4;
+    const int sp = HF ? 0 : (t - co4 * per_c4) / g8n;
+    const int sg8 = HF ? 0 : (t - co4 * per_c4) - sp * g8n;
+    const int da8 = HF ? (t / c4n) & 3 : 0;
+    const int hg = HF ? t / (4 * c4n) : 0;
+    // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel
+    const int rd_off = HF ? 8 * da8 * a.pitch + (hg * g.Co + 4 * co4) * 2
+                          : sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;
+    const int rd_step = HF ? a.pitch : g.Co * 2;
+    // bytes per channel plane: image H_out x W_out (W fold: Hout x out_row; HF: out_row x Hout, the plan is transposed)
+    const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;
 
     // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).
     const unsigned xcd = blockIdx.x % a.deal.parts, wg = blockIdx.x / a.deal.parts;
     const unsigned t_first = fc_deal_first_tile(a.deal, xcd, wg);  // the workgroup's first tile
 
-    // first pixel of the workgroup's current tile, advanced incrementally
+    // The workgroup's current tile.  W fold: 32 consecutive folded pixels from m0 = (img0, ho0, wo0), advanced
+    // incrementally.  HF: plan rows [32*ab, 32*ab + 32) of folded column wo0 in image img0 (tile index =
+    // (img0 * tiles_ab + ab) * Wf_out + wo0, folded column fastest: consecutive tiles share their 32 input rows),
+    // with ho0 = 32*ab; recomputed from the tile index.
     unsigned m0 = t_first * 32u;
-    unsigned wo0 = m0 % (unsigned)g.Wf_out, ho0, img0;
-    {
-        const unsigned rowid = m0 / (unsigned)g.Wf_out;
-        ho0 = rowid % (unsigned)g.Hout;
-        img0 = rowid / (unsigned)g.Hout;
-    }
+    unsigned wo0, ho0, img0;
+    auto place = [&](unsigned tile) {
+        if (HF) {
+            const unsigned rb = tile / (unsigned)g.Wf_out;  // (image, row block)
+            wo0 = tile - rb * (unsigned)g.Wf_out;
+            img0 = rb / a.tiles_ab;
+            ho0 = (rb - img0 * a.tiles_ab) * 32u;
+        } else {
+            wo0 = m0 % (unsigned)g.Wf_out;
+            const unsigned rowid = m0 / (unsigned)g.Wf_out;
+            ho0 = rowid % (unsigned)g.Hout;
+            img0 = rowid / (unsigned)g.Hout;
+        }
+    };
+    place(t_first);
+    // pixel i of the tile at (wo_base, ho_base, img_base): its coordinates, and whether it exists
     auto pixel = [&](unsigned wo_base, unsigned ho_base, unsigned img_base, unsigned i, unsigned &wo, unsigned &ho,
                      unsigned &img) {
+        if (HF) {
+            wo = wo_base;
+            ho = ho_base + i;
+            img = img_base;
+            return;
+        }
         const unsigned tt = wo_base + i;
         const unsigned q = small_div_n(tt, a.mgW, (unsigned)g.Wf_out);
         wo = tt - q * (unsigned)g.Wf_out;
@@ -175,7 +212,14 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         ho = hr - q2 * (unsigned)g.Hout;
         img = img_base + q2;
     };
+    unsigned cur_tile = t_first;
     auto advance = [&]() {
+        cur_tile += a.deal.stride;
+        if (HF) {
+            // past the last tile the position is never used for a store; keep it inside the tensor for the prefetch
+            place(cur_tile < a.MT ? cur_tile : a.MT - 1u);
+            return;
+        }
         m0 += a.deal.stride * 32u;
         wo0 += a.dW;
         unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
@@ -190,7 +234,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     auto load_tile = [&]() {
         unsigned wo, ho, img;
         pixel(wo0, ho0, img0, (unsigned)r, wo, ho, img);
-        const bool vm = m0 + (unsigned)r < (unsigned)g.M;
+        const bool vm = HF ? (cur_tile < a.MT && ho < (unsigned)g.Hout) : m0 + (unsigned)r < (unsigned)g.M;
         const int col0 = (int)wo * g.FC + e0;  // column of K-step 0 inside the input row
         const int pix0 = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col0;
 #pragma unroll
@@ -274,17 +318,27 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         // each does only after finishing its reads below.
         __syncthreads();
 
-        // ---- write out: y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8) for i = 0..3 ----
+        // ---- write out: W fold  y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8),
+        //                 HF      y[img][4*co4+i][F*wo + hg][ho0 + 8*da8 .. +8)   for i = 0..3 ----
         {
             unsigned wo, ho, img;
-            pixel(cur_wo0, cur_ho0, cur_img0, (unsigned)sp, wo, ho, img);
-            const bool ok = cur_m0 + (unsigned)sp < (unsigned)g.M;
-            const unsigned off0 =
-                2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
-                      wo * (unsigned)g.F + 8u * (unsigned)sg8);
+            bool ok;
+            unsigned off0;
+            if (HF) {
+                const unsigned h = cur_wo0 * (unsigned)g.F + (unsigned)hg;  // image row
+                const unsigned w0 = cur_ho0 + 8u * (unsigned)da8;          // first image column of the piece
+                img = cur_img0;
+                ok = h < (unsigned)g.out_row && w0 < (unsigned)g.Hout;     // Hout % 8 == 0: a piece is whole or absent
+                off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.out_row + h) * (unsigned)g.Hout + w0);
+            } else {
+                pixel(cur_wo0, cur_ho0, cur_img0, (unsigned)sp, wo, ho, img);
+                ok = cur_m0 + (unsigned)sp < (unsigned)g.M;
+                off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
+                             wo * (unsigned)g.F + 8u * (unsigned)sg8);
+            }
             u32x2 v[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const u32x2 *>(tb + rd_off + k * g.Co * 2);
+            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const u32x2 *>(tb + rd_off + k * rd_step);
 #pragma unroll
             for (int i = 0; i < kStores; ++i) {
                 u32x4 out;
@@ -302,24 +356,33 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
 static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
 
-template <typename TR, int KHM, int KSM>
+template <typename TR, int KHM, int KSM, bool HF>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
     NchwArgs a;
-    const int g8n = g.F / 8;
-    a.skew = g8n > 1 ? 256 / g8n : 0;
-    if (a.skew % 8 != 0) a.skew = 8;
-    a.pitch = g.NCo * 2 + g8n * a.skew + 8;
+    if (HF) {
+        // a thread of the write-out reads pixels 8 rows apart: a pitch of 16 bytes (mod 32) puts the two halves of
+        // a wave on disjoint banks
+        a.skew = 0;
+        a.pitch = g.NCo * 2 + 16;
+    } else {
+        const int g8n = g.F / 8;
+        a.skew = g8n > 1 ? 256 / g8n : 0;
+        if (a.skew % 8 != 0) a.skew = 8;
+        a.pitch = g.NCo * 2 + g8n * a.skew + 8;
+    }
     const unsigned lds_bytes = 2u * 32u * (unsigned)a.pitch;
     const unsigned threads = (unsigned)g.NCo;  // one wave per 64 columns
     // workgroups resident per compute unit: 16 waves at the register budget of the launch bounds, 160 KB of LDS
     unsigned per_cu = 1024u / threads;
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
-    a.MT = (unsigned)((g.M + 31) / 32);
+    a.tiles_ab = (unsigned)((g.Hout + 31) / 32);
+    a.MT = HF ? (unsigned)((long long)g.N * a.tiles_ab * g.Wf_out) : (unsigned)((g.M + 31) / 32);
     FcDevice dev;
     if (int e = fc_device(&dev)) return e;
-    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu, g.KH, g.Wf_out);
+    // HF: the Wf_out tiles of a row block share all their input rows; keep them in one chunk (one L2)
+    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu, g.KH, HF ? 8 * g.Wf_out : g.Wf_out);
     const long long S = 32LL * a.deal.stride, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
@@ -333,8 +396,8 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \
     do {                                                                                                     \
-        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL>>()) return e;            \
-        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL><<<blocks, threads, lds_bytes, st>>>(                   \
+        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF>>()) return e;        \
+        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF><<<blocks, threads, lds_bytes, st>>>(               \
             g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);                                 \
     } while (0)
     if (exact && g.relu) FC_GO(true, true);
@@ -345,21 +408,26 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     return (int)hipGetLastError();
 }
 
-template <typename TR>
+template <typename TR, bool HF>
 int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2>(g, ksteps, x, wp, bias, y, st);
-    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF>(g, ksteps, x, wp, bias, y, st);
     return (int)hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
-                               void *y, void *stream) {
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, const void *x, const void *w_pack,
+                               const void *bias, void *y, void *stream) {
     int ksteps = 0;
-    if (!fc_stream_nchw_ok(g, g.band, &ksteps)) return (int)hipErrorInvalidValue;
+    if (!fc_stream_nchw_ok(g, g.band, height_fold, &ksteps)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    if (dt == FOLDCONV_F16) return launch_any<F16Traits>(g, ksteps, x, w_pack, bias, y, st);
-    if (dt == FOLDCONV_BF16) return launch_any<BF16Traits>(g, ksteps, x, w_pack, bias, y, st);
+    if (height_fold) {
+        if (dt == FOLDCONV_F16) return launch_any<F16Traits, true>(g, ksteps, x, w_pack, bias, y, st);
+        if (dt == FOLDCONV_BF16) return launch_any<BF16Traits, true>(g, ksteps, x, w_pack, bias, y, st);
+    } else {
+        if (dt == FOLDCONV_F16) return launch_any<F16Traits, false>(g, ksteps, x, w_pack, bias, y, st);
+        if (dt == FOLDCONV_BF16) return launch_any<BF16Traits, false>(g, ksteps, x, w_pack, bias, y, st);
+    }
     return (int)hipErrorInvalidValue;
 }

@@ -54,10 +54,11 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
                           void *y, void *stream);
 int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack, const void *bias,
                          void *y, void *stream);
-// Streaming kernel that writes a channels-first output (g.out_row = W_out of the image); false if the
-// geometry does not fit it.
-bool fc_stream_nchw_ok(const ConvGeom &g, int band, int *ksteps);
-int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,
+// Streaming kernel that writes a channels-first output (g.out_row = the plan's unfolded W_out: the image's
+// W_out for a width fold, its H_out for a height fold, whose plan is that of the transposed image); false
+// if the geometry does not fit it.
+bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *ksteps);
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, const void *x, const void *w_pack,
                                const void *bias, void *y, void *stream);
 // Streaming kernel with the input tile staged through LDS (dense walks whose K extent fits the registers).
 bool fc_stream_lds_ok(const ConvGeom &g);

@@ -190,7 +190,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
         ConvGeom gn = g;  // the streaming kernel's channels-first variant sees W_out as the stored row
         gn.out_row = (int)W_out;
         int ks = 0;
-        s.out_nchw_fused = (s.conv_kernel == FC_KERNEL_STREAM && fc_stream_nchw_ok(gn, 1, &ks)) ? 1 : 0;
+        s.out_nchw_fused = (s.conv_kernel == FC_KERNEL_STREAM && fc_stream_nchw_ok(gn, 1, false, &ks)) ? 1 : 0;
     }
 
     const long long xpad_bytes = (long long)N * H * W * C_pad * eb;
@@ -235,8 +235,13 @@ extern "C" int foldconv_plan_nchw(int N, int C_in, int H, int W, int C_out, int 
     if (st != FOLDCONV_OK) return st;
     (*out)->fold_axis = fold_axis;
     (*out)->s.fold_axis = fold_axis;
-    // slots of a height fold are neighbours along h, not along the contiguous axis of y
-    if (fold_axis == FOLDCONV_FOLD_H) (*out)->s.out_nchw_fused = 0;
+    if (fold_axis == FOLDCONV_FOLD_H) {
+        // slots of a height fold are neighbours along h; the contiguous axis of y runs across the plan's rows
+        ConvGeom gn = (*out)->fold;
+        gn.out_row = (*out)->s.W_out;
+        int ks = 0;
+        (*out)->s.out_nchw_fused = ((*out)->s.conv_kernel == FC_KERNEL_STREAM && fc_stream_nchw_ok(gn, 1, true, &ks)) ? 1 : 0;
+    }
     return FOLDCONV_OK;
 }
 

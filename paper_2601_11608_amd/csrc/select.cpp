@@ -97,20 +97,26 @@ bool fc_stream_lds_ok(const ConvGeom &g) {
     return g.KH == 3 && g.kwin == 18 * 8;
 }
 
-bool fc_stream_nchw_ok(const ConvGeom &g, int band, int *ksteps) {
-    // g.out_row is the image's W_out here (elements per channel row of y).
-    // Whole 16-byte pieces of 8 slots, one wave per 64 columns, at most 16 waves, 4 channels per LDS read.
-    if (g.F % 8 != 0 || g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
+bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *ksteps) {
+    // g.out_row is the plan's unfolded W_out here: elements per channel row of y for a width fold, rows per
+    // channel plane for a height fold (the plan is the transposed image's).
+    // one wave per 64 columns, at most 16 waves, 4 channels per LDS read
+    if (g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
     if (g.NCo % 64 != 0 || g.NCo > 1024) return false;
-    // every slot of every folded output pixel is a real output column
-    if (g.out_row != g.F * g.Wf_out) return false;
+    if (height_fold) {
+        // 16-byte pieces run along the image width = the plan's rows: whole pieces of 8 columns
+        if (g.Hout % 8 != 0 || g.out_row > g.F * g.Wf_out) return false;
+    } else {
+        // whole 16-byte pieces of 8 slots; every slot of every folded output pixel is a real output column
+        if (g.F % 8 != 0 || g.out_row != g.F * g.Wf_out) return false;
+    }
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
-    // 32-bit byte offsets into x, y and the packed filter; 32-bit pixel index
+    // 32-bit byte offsets into x, y and the packed filter; 32-bit pixel and tile indices
     const long long x_elems = (long long)g.N * g.H * g.in_row;
     const long long y_elems = (long long)g.N * g.Co * g.Hout * g.out_row;
     const long long w_elems = (long long)g.KH * g.kwin * g.NCo;
     if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems >= (1LL << 31) - 64 || w_elems >= (1LL << 30)) return false;
-    if (g.M >= (1LL << 31)) return false;
+    if (g.M >= (1LL << 31) - (1LL << 20)) return false;
     const int ks = max_ksteps(g, band, 64);
     // compiled instances: (KH <= 1, two K-steps per kh) and (KH <= 3, one K-step per kh)
     if (!((g.KH <= 1 && ks <= 2) || (g.KH <= 3 && ks <= 1))) return false;

@@ -69,17 +69,32 @@ FUSED = [
 ]
 
 
+# Height folds (the plan is the transposed image's): N, C, H, W, Co, KH, KW, pad, F, bias, relu
+FUSED_H = [
+    (2, 3, 48, 32, 64, 3, 3, 1, 16, True, True),      # the headline structure, transposed: 16 waves, 3 folded columns
+    (3, 3, 48, 40, 64, 3, 3, 1, 16, True, False),     # W = 40: a full row block of 32 and a ragged one of 8
+    (1, 1, 64, 24, 32, 3, 3, 1, 8, False, True),      # 4 waves per workgroup
+    (2, 2, 40, 16, 16, 1, 1, 0, 4, True, True),       # 1 x 1 kernel, F = 4 (a height fold needs no multiple of 8)
+    (1, 1, 128, 8, 12, 3, 3, 1, 16, True, False),     # C_out = 12: 64-column waves straddle slots; one row block of 8
+    (5, 3, 224, 64, 64, 3, 3, 1, 16, True, True),     # 14 folded columns per row block, tiles dealt over the XCDs
+    (2, 2, 64, 25, 24, 3, 2, 0, 8, False, False),     # KW = 2 (the plan's KH): the guarded instance; VALID, W_out = 24, H_out = 62
+    (2, 1, 32, 18, 16, 3, 3, 0, 8, True, False),      # VALID: H_out = 30 is not a multiple of F: the last slots are dropped; W_out = 16
+    (3, 1, 16, 8, 8, 1, 1, 0, 16, True, False),       # one folded column, one row block
+]
+
+
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
-@pytest.mark.parametrize("case", FUSED, ids=lambda c: "x".join(map(str, c[:9])))
+@pytest.mark.parametrize("case", FUSED + FUSED_H, ids=lambda c: "x".join(map(str, c[:9])))
 def test_fused_nchw_output(fc, oracle, case, dt):
     N, C, H, W, Co, KH, KW, pad, F, hb, relu = case
     x = draw((N, C, H, W), dt, 41)
     w = (draw((Co, C, KH, KW), dt, 42) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
     b = draw((Co,), dt, 43).cuda() if hb else None
-    plan = fc.foldconv_plan_nchw(N, C, H, W, Co, KH, KW, pad, F, fc.FOLD_W, x.dtype)
+    axis = fc.FOLD_H if case in FUSED_H else fc.FOLD_W
+    plan = fc.foldconv_plan_nchw(N, C, H, W, Co, KH, KW, pad, F, axis, x.dtype)
     s = plan.shapes
     assert s.out_nchw_fused == 1, s.as_dict()
-    print("fused nchw", case, dt, flush=True)
+    print("fused nchw", "H" if axis == fc.FOLD_H else "W", case, dt, flush=True)
     xf, w_exp, ws = prepare(fc, plan, x, w)
     flags = fc.FLAG_RELU if relu else 0
     want = two_step(fc, plan, xf, w_exp, b, ws, flags)
@@ -89,7 +104,9 @@ def test_fused_nchw_output(fc, oracle, case, dt):
     assert torch.equal(got.view(torch.int16), want.view(torch.int16))
     # the compact filter gives the same bytes
     cws = torch.empty(int(s.filter_compact_bytes), dtype=torch.uint8, device="cuda")
-    fc.foldconv_pack_filter_compact(plan, w.permute(2, 3, 1, 0).contiguous().cuda(), cws)
+    # (the compact form is built from the HWIO filter of the plan's space: taps transposed for a height fold)
+    w_hwio = w.permute(3, 2, 1, 0) if axis == fc.FOLD_H else w.permute(2, 3, 1, 0)
+    fc.foldconv_pack_filter_compact(plan, w_hwio.contiguous().cuda(), cws)
     got_c = fused(fc, plan, xf, None, b, cws, flags | fc.FLAG_FILTER_COMPACT)
     torch.cuda.synchronize()
     assert torch.equal(got_c.view(torch.int16), want.view(torch.int16))
@@ -99,7 +116,8 @@ def test_fused_nchw_output(fc, oracle, case, dt):
         assert rel_l2_per_image(f64(got.cpu()).reshape(ref.shape), ref) <= TOL[dt]
 
 
-def test_fused_nchw_headline_layer_full_size(fc, oracle):
+@pytest.mark.parametrize("axis", ["W", "H"])
+def test_fused_nchw_headline_layer_full_size(fc, oracle, axis):
     """The headline layer (N=64, 3x224x224 -> 64 channels, fp16, F=16) written channels-first in one
     launch: identical to the two-step route everywhere, sampled images against the oracle."""
     from paper_2601_11608_amd import workloads as wl
@@ -108,9 +126,10 @@ def test_fused_nchw_headline_layer_full_size(fc, oracle):
     l = layers[0]
     xn = x.permute(0, 3, 1, 2).contiguous()
     wn = wts[0].permute(3, 2, 0, 1).contiguous()
-    plan = fc.foldconv_plan_nchw(l.N, l.C_in, l.H, l.W, l.C_out, l.KH, l.KW, l.pad, l.F, fc.FOLD_W, xn.dtype)
+    plan = fc.foldconv_plan_nchw(l.N, l.C_in, l.H, l.W, l.C_out, l.KH, l.KW, l.pad, l.F,
+                                 fc.FOLD_W if axis == "W" else fc.FOLD_H, xn.dtype)
     assert plan.shapes.out_nchw_fused == 1
-    print("fused nchw full size", flush=True)
+    print("fused nchw full size, fold", axis, flush=True)
     xf, w_exp, ws = prepare(fc, plan, xn, wn)
     b = bs[0].cuda()
     want = two_step(fc, plan, xf, w_exp, b, ws, 0)
@@ -125,8 +144,8 @@ def test_fused_nchw_headline_layer_full_size(fc, oracle):
 
 @pytest.mark.parametrize("axis", ["W", "H"])
 def test_channels_first_layer_runner(fc, oracle, axis):
-    """runner.ChannelsFirstLayer takes the fused route for a width fold and the two-step route for a
-    height fold; both match the oracle."""
+    """runner.ChannelsFirstLayer takes the fused route where the plan offers it (both folds here); both match
+    the oracle."""
     from paper_2601_11608_amd import workloads as wl
     from paper_2601_11608_amd.runner import ChannelsFirstLayer
 
@@ -135,7 +154,7 @@ def test_channels_first_layer_runner(fc, oracle, axis):
     w = (draw((l.C_out, l.C_in, 3, 3), "f16", 52) * (1.0 / np.sqrt(27))).to(torch.float16)
     b = draw((l.C_out,), "f16", 53)
     L = ChannelsFirstLayer(l, w, b, fc.FOLD_W if axis == "W" else fc.FOLD_H)
-    assert L.fused == (axis == "W")
+    assert L.fused
     y = L.forward(x.cuda(), L.new_output())
     torch.cuda.synchronize()
     ref = oracle.conv_direct_nchw(f64(x), f64(w), f64(b), 1, 1, True)
@@ -180,7 +199,8 @@ def test_fused_nchw_refusals(fc):
                        ((1, 12, 16, 32, 16, 3, 3, 1, 8), fc.FOLD_W),    # C_in = 12: five K-steps per kh
                        ((1, 3, 16, 30, 64, 3, 3, 0, 2), fc.FOLD_W),     # F not a multiple of 8
                        ((1, 3, 16, 32, 64, 3, 3, 0, 16), fc.FOLD_W),    # VALID: W_out = 30 is not F * W'_out
-                       ((2, 3, 32, 48, 64, 3, 3, 1, 16), fc.FOLD_H)]:   # height fold
+                       ((2, 3, 32, 44, 64, 3, 3, 1, 16), fc.FOLD_H),    # height fold, W_out = 44 not a multiple of 8
+                       ((1, 12, 32, 16, 16, 3, 3, 1, 8), fc.FOLD_H)]:   # height fold, C_in = 12: five K-steps per kh
         plan = fc.foldconv_plan_nchw(*args, axis, dt)
         s = plan.shapes
         assert s.out_nchw_fused == 0, args

@@ -173,7 +173,8 @@ def test_fused_channels_first_output_is_reported_in_the_plan(fc):
     assert fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes.out_nchw_fused == 1
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.bfloat16) == 1
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.float32) == 0    # fp32 runs the gather kernel
-    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 0      # slots are neighbours along h
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 1      # height fold: pieces run across the plan's rows
+    assert fused(64, 3, 224, 220, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 0      # ... which needs W_out in multiples of 8
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 4) == 0                       # F not a multiple of 8
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 32) == 0                      # F*C_out = 2048 > 1024
     assert fused(64, 3, 224, 224, 64, 3, 3, 0, 16) == 0                      # W_out = 222 is not F*W'_out
