@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 KERNEL_NAMES = ["gather", "tiled", "stream"]
-EXTRAS = ["dense_k", "padded", "repack", "compact_filter", "copies", "c5_stack", "small_configs", "gemm_1x1", "nchw",
+EXTRAS = ["dense_k", "padded", "pacing", "repack", "compact_filter", "copies", "c5_stack", "small_configs", "gemm_1x1", "nchw",
           "fold_choice", "operand_values"]
 
 
@@ -175,8 +175,10 @@ def fold_choice_table(fc, runner, wl, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # defaults: long enough a warm-up to be past the first ~10 ms after the GPU leaves idle, where its
+    # clocks dip and every memory-bound launch runs 10-30 % slower than before and after
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step (profiling runs)")
     ap.add_argument("--extras", default=",".join(EXTRAS), help="comma-separated subset of: " + ", ".join(EXTRAS))
@@ -292,6 +294,18 @@ def main():
             "folded_speedup_vs_conv_only": pc_ms / dev_ms,
         }
         del Lp, xpd
+    if "pacing" in want:
+        # the store pacing of the streaming kernel, A/B in steady state (200 warm-up launches each):
+        # the library's default, the same launch with FOLDCONV_FLAG_UNPACED, and a plain fill of y
+        _, on_ms = time_events(step, 100, 200)
+        _, off_ms = time_events(lambda: L.forward(xd, y, flags=fc.FLAG_UNPACED), 100, 200)
+        _, fill_ms = time_events(lambda: y.zero_(), 100, 200)
+        extras["pacing"] = {
+            "paced_ms": on_ms, "unpaced_ms": off_ms, "fill_ms": fill_ms,
+            "paced_GBps": algo_bytes / (on_ms * 1e-3) / 1e9, "unpaced_GBps": algo_bytes / (off_ms * 1e-3) / 1e9,
+            "fill_GBps": s.y_bytes / (fill_ms * 1e-3) / 1e9,
+            "note": "100 launches after 200 warm-ups each; fill = torch's zero_() on the %d MB output" % (s.y_bytes // 1000000),
+        }
     if "repack" in want:
         # per-call filter re-pack included (stateless call)
         _, r_ms = time_events(lambda: L.forward(xd, y, repack=True), max(20, args.steps // 2), 5)

@@ -74,11 +74,19 @@ enum {
     FOLDCONV_FLAG_FILTER_COMPACT = 16u, /* workspace holds the compact filter written by
                                          foldconv_pack_filter_compact (only the non-zero blocks
                                          of w'); w_exp is not read and may be NULL              */
-    FOLDCONV_FLAG_OUT_NCHW = 32u      /* write y channels-first, [N][C_out][H_out][W_out] of the
+    FOLDCONV_FLAG_OUT_NCHW = 32u,     /* write y channels-first, [N][C_out][H_out][W_out] of the
                                          image, in the same launch (no y' round trip through
                                          memory), for width- and height-folded plans.  Only where
                                          shapes.out_nchw_fused is 1, else
                                          FOLDCONV_ERR_UNSUPPORTED; excludes KEEP_FOLDED          */
+    FOLDCONV_FLAG_UNPACED = 64u       /* do not pace the store stream.  Long write-bound launches
+                                         of the streaming kernels hold each wave's store burst to a
+                                         schedule on the GPU's wall clock, set for a launch that
+                                         has the whole memory system to itself (about 10 % faster
+                                         than letting the waves overrun it).  A caller that runs
+                                         other work beside the launch, or wants to measure the
+                                         difference, passes this flag.  Same result either way.
+                                         Also accepted by conv_padded_forward                    */
 };
 
 /* Which image axis of a channels-first (NCHW) tensor is folded into the channels. */
@@ -319,8 +327,9 @@ FOLDCONV_API int foldconv_forward_static(foldconv_plan_t plan, const void *x_fol
  * copies live in workspace (shapes.padded_workspace_bytes).  With
  * FOLDCONV_FLAG_FILTER_PACKED only the input is padded again (the workspace
  * must be the one this plan's previous call prepared).  Flags other than
- * FOLDCONV_FLAG_RELU and FOLDCONV_FLAG_FILTER_PACKED are FOLDCONV_ERR_BADARG:
- * the reference path has no folded layout and no structural zeros to walk.
+ * FOLDCONV_FLAG_RELU, FOLDCONV_FLAG_FILTER_PACKED and FOLDCONV_FLAG_UNPACED
+ * are FOLDCONV_ERR_BADARG: the reference path has no folded layout and no
+ * structural zeros to walk.
  */
 FOLDCONV_API int conv_padded_forward(foldconv_plan_t plan, const void *x, const void *w, const void *bias,
                         void *y, void *workspace, size_t workspace_bytes, unsigned flags,

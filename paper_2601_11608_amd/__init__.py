@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     FLAG_FILTER_PACKED,
     FLAG_KEEP_FOLDED,
     FLAG_RELU,
+    FLAG_UNPACED,
     FOLD_H,
     FOLD_W,
     STATIC_SCRATCH_BYTES,

@@ -11,7 +11,7 @@ static int hip_status(int e) { return e == 0 ? FOLDCONV_OK : FOLDCONV_ERR_HIP; }
 
 static const unsigned kAllFlags =
     FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED |
-    FOLDCONV_FLAG_FILTER_COMPACT | FOLDCONV_FLAG_OUT_NCHW;
+    FOLDCONV_FLAG_FILTER_COMPACT | FOLDCONV_FLAG_OUT_NCHW | FOLDCONV_FLAG_UNPACED;
 
 extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
     if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
@@ -113,6 +113,7 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
     g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
     g.band = (flags & FOLDCONV_FLAG_DENSE_K) ? 0 : 1;
     g.has_bias = bias ? 1 : 0;
+    g.unpaced = (flags & FOLDCONV_FLAG_UNPACED) ? 1 : 0;
     g.out_row = (flags & FOLDCONV_FLAG_KEEP_FOLDED) ? g.Wf_out * g.NCo : s.W_out * s.C_out;
 
     int kernel = s.conv_kernel;
@@ -159,7 +160,7 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
                                    void *workspace, size_t workspace_bytes, unsigned flags, void *stream) {
     if (!plan_ok(plan) || !x || !w || !y) return FOLDCONV_ERR_BADARG;
     // the reference path has one walk, one layout and one filter form
-    if (flags & ~(unsigned)(FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_FILTER_PACKED)) return FOLDCONV_ERR_BADARG;
+    if (flags & ~(unsigned)(FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_FILTER_PACKED | FOLDCONV_FLAG_UNPACED)) return FOLDCONV_ERR_BADARG;
     const foldconv_shapes_t &s = plan->s;
     const size_t eb = (size_t)s.elem_bytes;
     if (!aligned(x, eb) || !aligned(w, eb) || !aligned(y, eb) || (bias && !aligned(bias, eb)))
@@ -194,6 +195,7 @@ extern "C" int conv_padded_forward(foldconv_plan_t plan, const void *x, const vo
     g.relu = (flags & FOLDCONV_FLAG_RELU) ? 1 : 0;
     g.band = 1;
     g.has_bias = bias ? 1 : 0;
+    g.unpaced = (flags & FOLDCONV_FLAG_UNPACED) ? 1 : 0;
     e = fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_pad, w_pad, w_pack, pad_out && bias ? b_pad : bias,
                        pad_out ? y_pad : y, stream);
     if (e) return FOLDCONV_ERR_HIP;

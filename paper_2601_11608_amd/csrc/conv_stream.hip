@@ -70,6 +70,7 @@ struct StreamArgs {
     unsigned mgW, mgH;  // ceil(2^32 / Wf_out), ceil(2^32 / Hout): exact division of small numerators
     unsigned x_bytes;   // extent of x for the range-checked buffer loads
     int linear_out;     // stored rows are exactly Wf_out*NCo long: y offset is m*NCo + n
+    unsigned pace;      // wall-clock ticks * 256 between a wave's store bursts, 0 = unpaced (see launch_inst)
 };
 
 // floor(t / d) for t < d + 64 and d < 65000, with mg = ceil(2^32 / d)
@@ -196,6 +197,9 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     }
     const unsigned long long y_rows_total = (unsigned long long)g.N * (unsigned)g.Hout;
 
+    // Store pacing: the wave's next store burst is not issued before this time (ticks * 256).
+    unsigned long long pace_next = a.pace ? (unsigned long long)wall_clock64() << 8 : 0ull;
+
     u32x4 xf[KHM][KSM];
     auto load_tile = [&](u32x4 (&dst)[KHM][KSM]) {
         const unsigned t = wo0 + (unsigned)r;
@@ -303,6 +307,11 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 *reinterpret_cast<u32x2 *>(slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * 2) = pk;
             }
         wave_lds_sync();
+        if (a.pace) {  // wave-uniform, scalar instructions only; the spin is bounded whatever the clock reads
+            for (int spin = 0; spin < 1024 && (long long)(((unsigned long long)wall_clock64() << 8) - pace_next) < 0; ++spin)
+                __builtin_amdgcn_s_sleep(1);
+            pace_next += a.pace;
+        }
         // Stores go through a range-checked buffer resource based at the tile's first output
         // row: lanes that have nothing to store (pixels past the end, cropped columns) use an
         // out-of-range offset and the hardware drops them.  No branch surrounds a store, so
@@ -368,6 +377,8 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.mgH = magic_for((unsigned)g.Hout);
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.linear_out = g.out_row == g.Wf_out * g.NCo ? 1 : 0;
+    a.pace = g.unpaced ? 0u : fc_store_pace(((double)g.N * g.H * g.in_row + (double)g.N * g.Hout * g.out_row) * (double)sizeof(T),
+                           (a.MT + a.deal.stride - 1) / a.deal.stride, dev.wall_khz);
     const unsigned blocks = (unsigned)((J * a.NG + 3) / 4) * a.deal.parts;
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                       \

@@ -63,6 +63,7 @@ struct NchwArgs {
     int pitch;            // bytes per pixel row of the assembled tile
     int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
     unsigned tiles_ab;    // HF: tiles per folded column, ceil(Hout / 32)
+    unsigned pace;        // wall-clock ticks * 256 between a workgroup's store bursts, 0 = unpaced (fc_store_pace)
 };
 
 template <int I, int N, class F>
@@ -259,6 +260,9 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     // issued ahead of the four stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int buf = 0;
+    // Store pacing (fc_store_pace): the wave's next store burst is not issued before this time (ticks * 256).
+    unsigned long long pace_next = a.pace ? (unsigned long long)wall_clock64() << 8 : 0ull;
+
     for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
         floatx16_t acc[NT];
         floatx16_t zero;
@@ -317,6 +321,11 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         // on, and no wave gets there before every wave has passed the next tile's barrier, which
         // each does only after finishing its reads below.
         __syncthreads();
+        if (a.pace) {  // wave-uniform, scalar instructions only; the spin is bounded whatever the clock reads
+            for (int spin = 0; spin < 1024 && (long long)(((unsigned long long)wall_clock64() << 8) - pace_next) < 0; ++spin)
+                __builtin_amdgcn_s_sleep(1);
+            pace_next += a.pace;
+        }
 
         // ---- write out: W fold  y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8),
         //                 HF      y[img][4*co4+i][F*wo + hg][ho0 + 8*da8 .. +8)   for i = 0..3 ----
@@ -392,6 +401,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
+    a.pace = g.unpaced ? 0u : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride, dev.wall_khz);
     const unsigned blocks = a.deal.J * a.deal.parts;
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \

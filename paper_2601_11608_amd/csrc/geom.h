@@ -37,6 +37,7 @@ struct ConvGeom {
     int in_row;        // elements per input row  (Wf*FC)
     int out_row;       // elements per stored output row (W_out*Co, or Wf_out*NCo when kept folded)
     int relu, band, has_bias;
+    int unpaced;       // leave the store stream of the streaming kernels unpaced (FOLDCONV_FLAG_UNPACED)
     int compact;       // the filter operand is the compact per-phase storage (see fc_compact_chunk)
     int cJ, cgcd;      // compact storage: chunks per (phase, kh), and gcd(C_in, 8)
     long long M;       // N*Hout*Wf_out

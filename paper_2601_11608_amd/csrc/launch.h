@@ -26,8 +26,25 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 struct FcDevice {
     unsigned cus;   // compute units
     unsigned xcds;  // accelerator dies, each with its own L2; workgroup b is placed on die b % xcds
+    unsigned wall_khz;  // rate of the constant clock wall_clock64() reads in a kernel, 0 = unknown
 };
 int fc_device(FcDevice *out);
+
+// --- store pacing of the persistent streaming kernels ---------------------------------------------
+// A write-dominated launch whose waves offer the memory system more than it can take runs 10-20 %
+// below what the same store stream reaches when every wave issues its bursts on a fixed schedule just
+// under that rate (a stand-alone stream of this kernel's store pattern, 411 MB: 69-72 us unpaced,
+// 59 us paced at 7.4 TB/s offered, 64 us at 7.8, 62 us for a plain fill).  The kernels therefore hold
+// each wave's store burst back until its slot on the constant wall clock.  Returns the interval between
+// a wave's bursts in wall-clock ticks * 256 when the launch moves `bytes` (input read once + output) in
+// `tiles_per_wave` equal steps at kPaceBytesPerSecond, or 0 (unpaced) for launches too short to reach
+// that steady state and where the clock rate is unknown.
+constexpr double kPaceBytesPerSecond = 7.35e12;
+inline unsigned fc_store_pace(double bytes, unsigned tiles_per_wave, unsigned wall_khz) {
+    if (wall_khz == 0 || tiles_per_wave < 12 || bytes < 64e6) return 0;
+    const double ticks = bytes / kPaceBytesPerSecond / tiles_per_wave * (double)wall_khz * 1e3;
+    return ticks * 256.0 < 4e9 ? (unsigned)(ticks * 256.0) : 0u;
+}
 
 // --- foldconv_forward's body (api.cpp).  remember_workspace = false: the packed filter goes to a
 //     buffer the caller of the ABI never sees, so the plan does not record it as a prepared workspace.

@@ -81,6 +81,45 @@ def test_config_matches_oracle(env, oracle, name, images, mode):
         a_in = a_out
 
 
+def test_store_pacing_changes_nothing(env):
+    """The headline layer at full size is long enough for the streaming kernels to pace their store
+    bursts on the wall clock (its run against the oracle above is a paced one).  With
+    FOLDCONV_FLAG_UNPACED the same bytes come out: folded path, zero-padded reference, channels-first
+    output.  Several launches each, so that waves do sleep in the paced ones."""
+    fc, runner, wl = env
+    layers, x, ws, bs = wl.make_config("c2")
+    l = layers[0]
+    L = runner.FoldedLayer(l, ws[0], bs[0])
+    xd = x.cuda()
+    y_paced, y_free = L.new_output(), L.new_output()
+    for _ in range(5):
+        L.forward(xd, y_paced)
+        L.forward(xd, y_free, flags=fc.FLAG_UNPACED)
+    torch.cuda.synchronize()
+    assert torch.equal(y_paced, y_free)
+    for _ in range(3):
+        L.forward_padded(xd, y_free)
+    s = L.plan.shapes
+    fc.conv_padded_forward(L.plan, xd, L.w, L.b, y_paced, L.ws_pad, fc.FLAG_FILTER_PACKED | fc.FLAG_UNPACED)
+    torch.cuda.synchronize()
+    assert torch.equal(y_paced, y_free)
+    with pytest.raises(fc.FoldconvError) as e:    # the reference path still rejects flags it does not honour
+        fc.conv_padded_forward(L.plan, xd, L.w, L.b, y_paced, L.ws_pad, fc.FLAG_DENSE_K)
+    assert e.value.status == -1
+    del y_paced, y_free
+    # channels-first output from the same launch
+    C = runner.ChannelsFirstLayer(l, ws[0].permute(3, 2, 0, 1).contiguous(), bs[0])
+    assert C.fused and s.N == 64
+    xc = x.permute(0, 3, 1, 2).contiguous().cuda()
+    y1, y2 = C.new_output(), C.new_output()
+    for _ in range(4):
+        C.forward(xc, y1)
+    flags = fc.FLAG_FILTER_PACKED | fc.FLAG_OUT_NCHW | fc.FLAG_UNPACED
+    fc.foldconv_forward(C.plan, C.x_fold, C.w_exp, C.b, y2, C.ws, flags)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
 def test_output_beyond_four_gigabytes(env, oracle):
     """Largest-size case: a tall-skinny product whose output (8.6 GB) needs more than 32 bits of
     byte offset, in the launch configuration the benchmark uses (packed filter, aliased fold).
