@@ -261,7 +261,9 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int buf = 0;
     // Store pacing (fc_store_pace): the wave's next store burst is not issued before this time (ticks * 256).
-    unsigned long long pace_next = a.pace ? (unsigned long long)wall_clock64() << 8 : 0ull;
+    // The workgroups start a fraction of an interval apart, so that their bursts do not all fall together.
+    unsigned long long pace_next =
+        a.pace ? ((unsigned long long)wall_clock64() << 8) + (unsigned long long)a.pace * blockIdx.x / gridDim.x : 0ull;
 
     for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
         floatx16_t acc[NT];
@@ -401,7 +403,14 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
-    a.pace = g.unpaced ? 0u : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride, dev.wall_khz);
+    // One workgroup per compute unit walks its tiles one after the other (load, multiply, assemble, barrier, write
+    // out): it cannot keep the schedule the channels-last kernel keeps, and a workgroup that is behind never sleeps.
+    // Offered at 6.8 TB/s it stays on schedule when launches follow one another (measured on the headline layer:
+    // 79 us unpaced and at 7.35 TB/s, 69-73 us at 6.6-7.0 TB/s).  Right after a different kernel (the fold pass of
+    // a channels-first caller) the launch still takes 80 us, whatever the rate and the spread of the start.
+    a.pace = g.unpaced ? 0u
+                       : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride,
+                                       dev.wall_khz, 6.8e12);
     const unsigned blocks = a.deal.J * a.deal.parts;
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \

@@ -366,7 +366,10 @@ conv_tiled_kernel(ConvGeom g, TiledArgs a, const typename TR::T *__restrict__ x,
                 if (oc + 8u <= (unsigned)g.out_row) {
                     const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * EPITCH + ch * 16);
                     const unsigned long long off8 = ((unsigned long long)rowid * (unsigned)g.out_row + oc) >> 3;
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(y) + off8);
+                    // a plain store: these layers are not bound by their output stream, and the layer that
+                    // follows finds y in the caches (the five-layer stack runs 1 % faster than with
+                    // non-temporal stores, its zero-padded reference 3.5 %)
+                    reinterpret_cast<u32x4 *>(y)[off8] = v;
                 }
             }
         }

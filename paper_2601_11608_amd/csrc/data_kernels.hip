@@ -235,7 +235,9 @@ nchw_to_fold_kernel(const U *__restrict__ x, U *__restrict__ xf, NchwMap m, int 
         if (vec && e + EPC <= m.total) {
             u32x4 out;
             __builtin_memcpy(&out, v, 16);
-            __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(xf) + i);
+            // a plain store: the convolution that follows reads x' at once, out of the caches this leaves it in
+            // (written non-temporally, the same launch took 12 us longer on the headline layer)
+            reinterpret_cast<u32x4 *>(xf)[i] = out;
         } else {
 #pragma unroll
             for (int j = 0; j < EPC; ++j)

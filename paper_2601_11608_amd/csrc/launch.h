@@ -40,9 +40,10 @@ int fc_device(FcDevice *out);
 // `tiles_per_wave` equal steps at kPaceBytesPerSecond, or 0 (unpaced) for launches too short to reach
 // that steady state and where the clock rate is unknown.
 constexpr double kPaceBytesPerSecond = 7.35e12;
-inline unsigned fc_store_pace(double bytes, unsigned tiles_per_wave, unsigned wall_khz) {
+inline unsigned fc_store_pace(double bytes, unsigned tiles_per_wave, unsigned wall_khz,
+                              double bytes_per_second = kPaceBytesPerSecond) {
     if (wall_khz == 0 || tiles_per_wave < 12 || bytes < 64e6) return 0;
-    const double ticks = bytes / kPaceBytesPerSecond / tiles_per_wave * (double)wall_khz * 1e3;
+    const double ticks = bytes / bytes_per_second / tiles_per_wave * (double)wall_khz * 1e3;
     return ticks * 256.0 < 4e9 ? (unsigned)(ticks * 256.0) : 0u;
 }
 
