@@ -62,7 +62,8 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 //     launch-and-drain overhead + max(memory time, matrix time) + filter term,
 // with the rates these kernels sustain on MI355X (fitted to the timings of every legal power-of-two
 // fold factor of the benchmark layers, rotating buffers, graph replay):
-//   * memory: x + y + filter bytes at 6.2 TB/s (of the 8 TB/s HBM peak).  On the streaming kernel a wave
+//   * memory: x + y + filter bytes at 6.2 TB/s (of the 8 TB/s HBM peak), 7.0 TB/s for launches of the streaming
+//     kernel long enough to pace their store stream (64 MB and more).  On the streaming kernel a wave
 //     owns 64 (or 128) output columns, so y counts at F*C_out rounded up to whole waves: idle
 //     lanes store nothing but take their turn (tile alignment);
 //   * matrix: issued MFMA flops (band walk, tile padding and the rank-1 bias product included) at
@@ -75,7 +76,7 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 static double model_seconds(const foldconv_shapes_t &s, int wave_columns) {
     const double x = (double)s.x_bytes, y = (double)s.y_bytes;
     const double wf = s.prefer_compact ? (double)s.filter_compact_bytes : (double)s.w_exp_bytes;
-    const double hbm = 6.2e12;
+    const double hbm = (s.conv_kernel == FC_KERNEL_STREAM && x + y >= 64e6) ? 7.0e12 : 6.2e12;
     double overhead, rate, y_eff = y;
     if (s.conv_kernel == FC_KERNEL_STREAM) {
         overhead = 4.5e-6;
