@@ -405,9 +405,9 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.ksteps = ksteps;
     // One workgroup per compute unit walks its tiles one after the other (load, multiply, assemble, barrier, write
     // out): it cannot keep the schedule the channels-last kernel keeps, and a workgroup that is behind never sleeps.
-    // Offered at 6.8 TB/s it stays on schedule when launches follow one another (measured on the headline layer:
-    // 79 us unpaced and at 7.35 TB/s, 69-73 us at 6.6-7.0 TB/s).  Right after a different kernel (the fold pass of
-    // a channels-first caller) the launch still takes 80 us, whatever the rate and the spread of the start.
+    // Offered at 6.8 TB/s it stays on schedule (measured on the headline layer: 79 us unpaced and at 7.35 TB/s,
+    // 69-73 us at 6.6-7.0 TB/s), provided its input is in the caches when it starts: after a fold pass that wrote
+    // x' non-temporally the launch took 81 us whatever the rate, which is why that pass writes with plain stores.
     a.pace = g.unpaced ? 0u
                        : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride,
                                        dev.wall_khz, 6.8e12);
