@@ -117,7 +117,7 @@ typedef struct foldconv_shapes_s {
                                        16-bit plan on the streaming kernel, F*C_out a multiple of
                                        64 and at most 1024, C_out a multiple of 4, y below 4 GiB;
                                        width fold: F a multiple of 8 and W_out == F*W_out_fold;
-                                       height fold: the image's W_out a multiple of 8           */
+                                       height fold: the image's W_out a multiple of 8, F even   */
     int32_t prefer_compact;         /* hint: 1 when foldconv_forward is expected to run faster from
                                        the compact filter than from packed w' (large-K layers whose
                                        packed band would crowd the input out of the L2: measured

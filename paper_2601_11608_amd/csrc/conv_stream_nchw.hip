@@ -21,7 +21,10 @@
 // consecutive plan rows at one folded column b' (instead of 32 consecutive folded pixels of a
 // row), and a thread of the write-out reads the same four channels of one slot from eight
 // neighbouring pixels: again four 16-byte pieces of 8 consecutive image columns, now at image
-// row h = F*b' + g.
+// row h = F*b' + g.  Two such tiles, one above the other, are assembled in the two LDS buffers
+// before either is written out, so that eight neighbouring lanes store 64 consecutive image
+// columns of a channel row: whole 128-byte lines (half lines, written tile by tile, cost a
+// quarter of the launch).
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
 // w = F w' + f (h = F h' + f for a height fold), applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
@@ -54,7 +57,7 @@ __device__ __forceinline__ unsigned pack2n<BF16Traits>(float a, float b) {
 constexpr unsigned kOutOfRangeN = 0xfffffff0u;  // beyond any resource extent used here (extents stay below 2^32 - 64)
 
 struct NchwArgs {
-    unsigned MT;          // 32-pixel M tiles
+    unsigned MT;          // 32-pixel M tiles (HF: pairs of them, 64 plan rows of one folded column)
     FcDeal deal;          // how M tiles are dealt to the XCDs: deal.J workgroups per XCD, one tile each at a time
     unsigned dW, dH, dI;  // the stride of a workgroup's tile walk, 32*deal.stride pixels, as (folded column, row, image) steps
     unsigned mgW, mgH;    // ceil(2^32 / Wf_out), ceil(2^32 / Hout)
@@ -62,7 +65,7 @@ struct NchwArgs {
     int ksteps;           // 16-wide K-steps per kh actually walked (<= KSM)
     int pitch;            // bytes per pixel row of the assembled tile
     int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
-    unsigned tiles_ab;    // HF: tiles per folded column, ceil(Hout / 32)
+    unsigned tiles_ab;    // HF: tile pairs per folded column, ceil(Hout / 64)
     unsigned pace;        // wall-clock ticks * 256 between a workgroup's store bursts, 0 = unpaced (fc_store_pace)
 };
 
@@ -87,7 +90,6 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     using T = typename TR::T;
     using Vec = typename TR::Vec;
     constexpr int NT = 2, COLS = 64;
-    constexpr int kStores = 4;  // 16-byte stores per thread and tile, issued unconditionally
     extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];  // two tiles of 32 * pitch bytes
 
     const int t = threadIdx.x;
@@ -153,20 +155,21 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     }
     const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(y, 0, (int)a.y_bytes, 0x00020000);
 
-    // ---- this thread's share of the write-out: pixel sp of the tile, slots [8*sg8, 8*sg8+8),
-    //      channels [4*co4, 4*co4+4): 32 * (F/8) threads per channel quadruple, C_out/4 quadruples
-    //      (HF: pixels [8*da8, 8*da8+8) of the tile, slot hg, channels [4*co4, 4*co4+4): C_out/4 threads per
-    //      (slot, pixel group), consecutive lanes on consecutive channel quadruples)
+    // ---- this thread's share of the write-out.  W fold: pixel sp of the tile, slots [8*sg8, 8*sg8+8),
+    //      channels [4*co4, 4*co4+4): 32 * (F/8) threads per channel quadruple, C_out/4 quadruples.
+    //      HF: pixels [8*da8, 8*da8+8) of the tile pair (da8 < 4: first tile, else second), slots hg and
+    //      hg + F/2 in turn, channels [4*co4, 4*co4+4); da8 runs fastest over the lanes, so eight lanes
+    //      store 128 consecutive bytes of a channel row.
     const int g8n = HF ? 1 : g.F >> 3;
     const int per_c4 = 32 * g8n;
     const int c4n = g.Co >> 2;
-    const int co4 = HF ? t % c4n : t / per_c4;
+    const int co4 = HF ? (t >> 3) % c4n : t / per_c4;
     const int sp = HF ? 0 : (t - co4 * per_c4) / g8n;
     const int sg8 = HF ? 0 : (t - co4 * per_c4) - sp * g8n;
-    const int da8 = HF ? (t / c4n) & 3 : 0;
-    const int hg = HF ? t / (4 * c4n) : 0;
-    // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel
-    const int rd_off = HF ? 8 * da8 * a.pitch + (hg * g.Co + 4 * co4) * 2
+    const int da8 = HF ? t & 7 : 0;
+    const int hg = HF ? t / (8 * c4n) : 0;  // below F/2: the block has F*C_out threads
+    // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel, + (F/2) * C_out * 2 for the second slot
+    const int rd_off = HF ? ((da8 >> 2) * 32 + 8 * (da8 & 3)) * a.pitch + (hg * g.Co + 4 * co4) * 2
                           : sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;
     const int rd_step = HF ? a.pitch : g.Co * 2;
     // bytes per channel plane: image H_out x W_out (W fold: Hout x out_row; HF: out_row x Hout, the plan is transposed)
@@ -177,17 +180,21 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     const unsigned t_first = fc_deal_first_tile(a.deal, xcd, wg);  // the workgroup's first tile
 
     // The workgroup's current tile.  W fold: 32 consecutive folded pixels from m0 = (img0, ho0, wo0), advanced
-    // incrementally.  HF: plan rows [32*ab, 32*ab + 32) of folded column wo0 in image img0 (tile index =
-    // (img0 * tiles_ab + ab) * Wf_out + wo0, folded column fastest: consecutive tiles share their 32 input rows),
-    // with ho0 = 32*ab; recomputed from the tile index.
+    // incrementally.  HF: tile pair `tile` = (img0 * tiles_ab + pair) * Wf_out + wo0 (folded column fastest:
+    // consecutive pairs share their 64 input rows); its half `sub` holds plan rows [ho0, ho0 + 32),
+    // ho0 = 64 * pair + 32 * sub.  A half that starts at or beyond Hout reads zeros and stores nothing.
     unsigned m0 = t_first * 32u;
     unsigned wo0, ho0, img0;
-    auto place = [&](unsigned tile) {
+    unsigned cur_tile = t_first;
+    auto place = [&](unsigned tile, unsigned sub) {
         if (HF) {
-            const unsigned rb = tile / (unsigned)g.Wf_out;  // (image, row block)
-            wo0 = tile - rb * (unsigned)g.Wf_out;
+            cur_tile = tile;
+            // past the last pair the position is never used for a store; keep it inside the tensor for the prefetch
+            const unsigned tl = tile < a.MT ? tile : a.MT - 1u;
+            const unsigned rb = tl / (unsigned)g.Wf_out;  // (image, pair)
+            wo0 = tl - rb * (unsigned)g.Wf_out;
             img0 = rb / a.tiles_ab;
-            ho0 = (rb - img0 * a.tiles_ab) * 32u;
+            ho0 = (rb - img0 * a.tiles_ab) * 64u + 32u * sub;
         } else {
             wo0 = m0 % (unsigned)g.Wf_out;
             const unsigned rowid = m0 / (unsigned)g.Wf_out;
@@ -195,7 +202,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             img0 = rowid / (unsigned)g.Hout;
         }
     };
-    place(t_first);
+    place(t_first, 0);
     // pixel i of the tile at (wo_base, ho_base, img_base): its coordinates, and whether it exists
     auto pixel = [&](unsigned wo_base, unsigned ho_base, unsigned img_base, unsigned i, unsigned &wo, unsigned &ho,
                      unsigned &img) {
@@ -213,14 +220,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         ho = hr - q2 * (unsigned)g.Hout;
         img = img_base + q2;
     };
-    unsigned cur_tile = t_first;
-    auto advance = [&]() {
-        cur_tile += a.deal.stride;
-        if (HF) {
-            // past the last tile the position is never used for a store; keep it inside the tensor for the prefetch
-            place(cur_tile < a.MT ? cur_tile : a.MT - 1u);
-            return;
-        }
+    auto advance = [&]() {  // W fold only
         m0 += a.deal.stride * 32u;
         wo0 += a.dW;
         unsigned c = wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
@@ -257,16 +257,24 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     load_tile();
     // Drain the first tile's loads here: the loop head then only ever waits for loads that were
-    // issued ahead of the four stores of the previous tile, and leaves those stores in flight.
+    // issued ahead of the stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    int buf = 0;
     // Store pacing (fc_store_pace): the wave's next store burst is not issued before this time (ticks * 256).
     // The workgroups start a fraction of an interval apart, so that their bursts do not all fall together.
     unsigned long long pace_next =
         a.pace ? ((unsigned long long)wall_clock64() << 8) + (unsigned long long)a.pace * blockIdx.x / gridDim.x : 0ull;
+    auto pace = [&]() {
+        if (a.pace) {  // wave-uniform, scalar instructions only; the spin is bounded whatever the clock reads
+            for (int spin = 0; spin < 1024 && (long long)(((unsigned long long)wall_clock64() << 8) - pace_next) < 0; ++spin)
+                __builtin_amdgcn_s_sleep(1);
+            pace_next += a.pace;
+        }
+    };
 
-    for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
-        floatx16_t acc[NT];
+    // The fragments in xf times the resident filter, bias included.  STORES_BEHIND: the stores the wave issued
+    // after the loads of xf.
+    auto multiply = [&](floatx16_t (&acc)[NT], auto stores_behind) {
+        constexpr int STORES_BEHIND = decltype(stores_behind)::value;
         floatx16_t zero;
 #pragma unroll
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
@@ -286,24 +294,18 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             if (EXACT || (kh < KH && ks < KS)) {
                 // Vector-memory operations retire in issue order.  Behind this fragment's load the
                 // wave has issued the remaining fragment loads of the tile and then exactly
-                // kStores stores, so the fragment has landed once at most that many operations
+                // STORES_BEHIND stores, so the fragment has landed once at most that many operations
                 // are outstanding.  Instances with run-time K guards have drained everything above.
-                constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) + kStores : 0;
+                constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) + STORES_BEHIND : 0;
                 asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");
                 const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
             }
         });
-        const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_ho0 = ho0, cur_img0 = img0;
-        advance();
-        // The next tile's input stays in flight across the write-out.  After the last tile this
-        // fetches a tile that is never used; every lane's address is either inside x or out of
-        // the resource's range, so the load is always safe.
-        load_tile();
-
-        // ---- assemble the tile in LDS: pixel rows of F*C_out columns ----
-        unsigned char *tb = tile_lds + buf * (32 * a.pitch);
+    };
+    // Round (and clamp) the wave's 32 x 64 results into pixel rows of F*C_out columns at tb.
+    auto assemble = [&](const floatx16_t (&acc)[NT], unsigned char *tb) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -319,49 +321,86 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 const int slot8 = (n / g.Co) >> 3;
                 *reinterpret_cast<u32x2 *>(tb + r * a.pitch + n * 2 + slot8 * a.skew) = pk;
             }
-        // One barrier per tile is enough with two buffers: this buffer is written again two tiles
-        // on, and no wave gets there before every wave has passed the next tile's barrier, which
-        // each does only after finishing its reads below.
-        __syncthreads();
-        if (a.pace) {  // wave-uniform, scalar instructions only; the spin is bounded whatever the clock reads
-            for (int spin = 0; spin < 1024 && (long long)(((unsigned long long)wall_clock64() << 8) - pace_next) < 0; ++spin)
-                __builtin_amdgcn_s_sleep(1);
-            pace_next += a.pace;
+    };
+    // Eight 8-byte reads at src (four channels of eight neighbouring slots or pixels), regrouped into four
+    // 16-byte pieces of eight consecutive image columns, one per channel plane from off0 on.
+    auto write_out = [&](const unsigned char *src, unsigned off0, bool ok) {
+        u32x2 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const u32x2 *>(src + k * rd_step);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            u32x4 out;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned lo = v[2 * j][i >> 1], hi = v[2 * j + 1][i >> 1];
+                out[j] = (i & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(out, yr, ok ? off0 + (unsigned)i * plane_b : kOutOfRangeN, 0, 2 /* nt */);
         }
+    };
 
-        // ---- write out: W fold  y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8),
-        //                 HF      y[img][4*co4+i][F*wo + hg][ho0 + 8*da8 .. +8)   for i = 0..3 ----
-        {
-            unsigned wo, ho, img;
-            bool ok;
-            unsigned off0;
-            if (HF) {
-                const unsigned h = cur_wo0 * (unsigned)g.F + (unsigned)hg;  // image row
-                const unsigned w0 = cur_ho0 + 8u * (unsigned)da8;          // first image column of the piece
-                img = cur_img0;
-                ok = h < (unsigned)g.out_row && w0 < (unsigned)g.Hout;     // Hout % 8 == 0: a piece is whole or absent
-                off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.out_row + h) * (unsigned)g.Hout + w0);
-            } else {
-                pixel(cur_wo0, cur_ho0, cur_img0, (unsigned)sp, wo, ho, img);
-                ok = cur_m0 + (unsigned)sp < (unsigned)g.M;
-                off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
-                             wo * (unsigned)g.F + 8u * (unsigned)sg8);
-            }
-            u32x2 v[8];
+    if constexpr (HF) {
+        // Per tile pair: both halves multiplied and assembled (one LDS buffer each), one barrier, eight stores
+        // per thread, and a second barrier before the next pair's first half overwrites buffer 0.  The input
+        // of the half after the current one is always in flight: behind the loads of a first half lie the
+        // eight stores of the pair before it, behind those of a second half none.
+        unsigned char *const tb0 = tile_lds, *const tb1 = tile_lds + 32 * a.pitch;
+        for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
+            floatx16_t acc[NT];
+            multiply(acc, std::integral_constant<int, 8>{});
+            const unsigned cur_wo0 = wo0, cur_ho0 = ho0, cur_img0 = img0;  // first half: ho0 = 64 * pair
+            place(mt, 1);
+            load_tile();
+            __syncthreads();  // every wave has finished reading the previous pair out of both buffers
+            assemble(acc, tb0);
+            multiply(acc, std::integral_constant<int, 0>{});
+            // After the workgroup's last pair this fetches a tile that is never used; every lane's address is
+            // either inside x or out of the resource's range, so the load is always safe.
+            place(mt + a.deal.stride, 0);
+            load_tile();
+            assemble(acc, tb1);
+            __syncthreads();
+            pace();
+            // ---- write out y[img][4*co4+i][F*wo + hg (+ F/2)][ho0 + 8*da8 .. +8) for i = 0..3 ----
+            const unsigned w0 = cur_ho0 + 8u * (unsigned)da8;  // first image column of the piece
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = *reinterpret_cast<const u32x2 *>(tb + rd_off + k * rd_step);
-#pragma unroll
-            for (int i = 0; i < kStores; ++i) {
-                u32x4 out;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const unsigned lo = v[2 * j][i >> 1], hi = v[2 * j + 1][i >> 1];
-                    out[j] = (i & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-                }
-                __builtin_amdgcn_raw_buffer_store_b128(out, yr, ok ? off0 + (unsigned)i * plane_b : kOutOfRangeN, 0, 2 /* nt */);
+            for (int half = 0; half < 2; ++half) {
+                const unsigned slot = (unsigned)hg + (unsigned)half * ((unsigned)g.F >> 1);
+                const unsigned h = cur_wo0 * (unsigned)g.F + slot;  // image row
+                const bool ok = h < (unsigned)g.out_row && w0 < (unsigned)g.Hout;  // Hout % 8 == 0: a piece is whole or absent
+                const unsigned off0 =
+                    2u * (((cur_img0 * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.out_row + h) * (unsigned)g.Hout + w0);
+                write_out(tile_lds + rd_off + half * ((g.F >> 1) * g.Co * 2), off0, ok);
             }
         }
-        buf ^= 1;
+    } else {
+        int buf = 0;
+        for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
+            floatx16_t acc[NT];
+            multiply(acc, std::integral_constant<int, 4>{});
+            const unsigned cur_m0 = m0, cur_wo0 = wo0, cur_ho0 = ho0, cur_img0 = img0;
+            advance();
+            // The next tile's input stays in flight across the write-out.  After the last tile this
+            // fetches a tile that is never used; every lane's address is either inside x or out of
+            // the resource's range, so the load is always safe.
+            load_tile();
+            unsigned char *tb = tile_lds + buf * (32 * a.pitch);
+            assemble(acc, tb);
+            // One barrier per tile is enough with two buffers: this buffer is written again two tiles
+            // on, and no wave gets there before every wave has passed the next tile's barrier, which
+            // each does only after finishing its reads below.
+            __syncthreads();
+            pace();
+            // ---- write out y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8) for i = 0..3 ----
+            unsigned wo, ho, img;
+            pixel(cur_wo0, cur_ho0, cur_img0, (unsigned)sp, wo, ho, img);
+            const bool ok = cur_m0 + (unsigned)sp < (unsigned)g.M;
+            const unsigned off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
+                                        wo * (unsigned)g.F + 8u * (unsigned)sg8);
+            write_out(tb + rd_off, off0, ok);
+            buf ^= 1;
+        }
     }
 }
 
@@ -372,10 +411,10 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     using T = typename TR::T;
     NchwArgs a;
     if (HF) {
-        // a thread of the write-out reads pixels 8 rows apart: a pitch of 16 bytes (mod 32) puts the two halves of
-        // a wave on disjoint banks
+        // a thread of the write-out reads pixels 8 rows apart and eight neighbouring lanes read pixels 8k .. 8k+7
+        // of the pair: with a pitch of 8 bytes (mod 32) the lanes of a wave spread over all banks in both phases
         a.skew = 0;
-        a.pitch = g.NCo * 2 + 16;
+        a.pitch = g.NCo * 2 + 8;
     } else {
         const int g8n = g.F / 8;
         a.skew = g8n > 1 ? 256 / g8n : 0;
@@ -388,7 +427,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     unsigned per_cu = 1024u / threads;
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
-    a.tiles_ab = (unsigned)((g.Hout + 31) / 32);
+    a.tiles_ab = (unsigned)((g.Hout + 63) / 64);
     a.MT = HF ? (unsigned)((long long)g.N * a.tiles_ab * g.Wf_out) : (unsigned)((g.M + 31) / 32);
     FcDevice dev;
     if (int e = fc_device(&dev)) return e;

@@ -104,8 +104,9 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
     if (g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
     if (g.NCo % 64 != 0 || g.NCo > 1024) return false;
     if (height_fold) {
-        // 16-byte pieces run along the image width = the plan's rows: whole pieces of 8 columns
-        if (g.Hout % 8 != 0 || g.out_row > g.F * g.Wf_out) return false;
+        // 16-byte pieces run along the image width = the plan's rows: whole pieces of 8 columns; a thread of the
+        // write-out serves the slots hg and hg + F/2
+        if (g.Hout % 8 != 0 || g.F % 2 != 0 || g.out_row > g.F * g.Wf_out) return false;
     } else {
         // whole 16-byte pieces of 8 slots; every slot of every folded output pixel is a real output column
         if (g.F % 8 != 0 || g.out_row != g.F * g.Wf_out) return false;
