@@ -246,6 +246,79 @@ nchw_to_fold_kernel(const U *__restrict__ x, U *__restrict__ xf, NchwMap m, int 
     }
 }
 
+// The same re-index for 16-bit tensors through LDS, 16 bytes per lane on both sides.  A workgroup takes
+// TA consecutive plan rows a of one image, every b and c: in x' that is one contiguous run of TA*B*C
+// elements; in x it is C*R runs of L contiguous elements (width fold: R = TA rows of L = B elements per
+// channel plane; height fold: R = B image rows, of which the tile takes L = TA columns).  The runs go
+// to LDS as [c][a][b] (width fold) or [c][b][a] (height fold) with an odd dword pitch, and each thread
+// gathers the eight elements of a piece of x' from there.
+struct NchwTile {
+    int C, A, B;            // channels, plan-space rows and columns
+    long long sC, sA, sB;   // element strides of (c, a, b) inside one NCHW image; one of sA, sB is 1
+    int TA;                 // plan rows per tile (a multiple of 8 when sA == 1)
+    int tiles_a;            // ceil(A / TA)
+    int R, L;               // runs per channel and elements per run (see above)
+    int la, lb, LC;         // LDS element strides of a, b and c
+};
+
+__global__ void __launch_bounds__(kThreads)
+nchw_to_fold_tile_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ xf, NchwTile m) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t fold_lds[];
+    const int t = threadIdx.x;
+    const long long n = blockIdx.x / m.tiles_a;
+    const int a0 = (int)(blockIdx.x - n * m.tiles_a) * m.TA;
+    const int ta = m.A - a0 < m.TA ? m.A - a0 : m.TA;  // rows of this tile
+    const uint16_t *img = x + n * (long long)m.C * m.A * m.B;
+    const bool w_fold = m.sB == 1;
+    // ---- runs of x -> LDS, 16 bytes per load, four 4-byte LDS writes (the pitch is only 4-byte aligned) ----
+    const int chunks_per_run = m.L >> 3;
+    const int runs = m.C * m.R;
+    for (int q = t; q < runs * chunks_per_run; q += kThreads) {
+        const int run = q / chunks_per_run, k8 = (q - run * chunks_per_run) << 3;
+        const int c = run / m.R, r = run - c * m.R;
+        long long src;
+        int dst;
+        bool in;
+        if (w_fold) {  // r = row of the tile, k8 = first column b of the chunk
+            in = r < ta;
+            src = c * m.sC + (long long)(a0 + r) * m.sA + k8;
+            dst = c * m.LC + r * m.la + k8;
+        } else {       // r = image row b, k8 = first row a of the chunk inside the tile
+            in = k8 < ta;  // A is a multiple of 8: a chunk is whole or absent
+            src = c * m.sC + (long long)r * m.sB + a0 + k8;
+            dst = c * m.LC + r * m.lb + k8;
+        }
+        if (in) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(img + src);
+            unsigned *d = reinterpret_cast<unsigned *>(fold_lds + dst);
+            d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+        }
+    }
+    __syncthreads();
+    // ---- pieces of x': eight consecutive (b, c) elements of the tile's contiguous run ----
+    const int row = m.B * m.C;                 // elements per plan row of x', a multiple of 8
+    const int pieces = ta * (row >> 3);
+    u32x4 *out = reinterpret_cast<u32x4 *>(xf + ((n * m.A + a0) * (long long)row));
+    for (int p = t; p < pieces; p += kThreads) {
+        const int e = p << 3;
+        int a = e / row;
+        const int qq = e - a * row;
+        int b = qq / m.C, c = qq - b * m.C;
+        unsigned v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            v[j] = fold_lds[c * m.LC + a * m.la + b * m.lb];
+            if (++c == m.C) {
+                c = 0;
+                if (++b == m.B) { b = 0; ++a; }
+            }
+        }
+        u32x4 o = {v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        // a plain store: the convolution that follows reads x' at once, out of the caches this leaves it in
+        out[p] = o;
+    }
+}
+
 // Output: y'[n][a][b][co] (row pitch in b given, columns b >= B cropped: the ragged
 // reconstruct) -> y[n][co][himg][wimg].  A workgroup moves a tile of 64 image columns x 64
 // channels of one image row through LDS: 16-byte loads along co, eight 2-byte LDS reads per
@@ -475,6 +548,31 @@ int fc_launch_fold_nchw(const foldconv_plan_s *p, const void *x, void *x_fold, v
     m.sC = (long long)s.H * s.W;
     if (p->fold_axis == FOLDCONV_FOLD_H) { m.sA = 1; m.sB = s.H; }   // image is [C][W_plan = H_img][H_plan = W_img]
     else { m.sA = s.W; m.sB = 1; }
+    // 16-bit tensors whose rows split into whole 16-byte pieces on both sides go through LDS
+    if (s.elem_bytes == 2 && ((uintptr_t)x | (uintptr_t)x_fold) % 16 == 0 && ((long long)m.B * m.C) % 8 == 0 &&
+        (m.sB == 1 ? m.B % 8 == 0 : m.A % 8 == 0)) {
+        NchwTile tl;
+        tl.C = m.C; tl.A = m.A; tl.B = m.B; tl.sC = m.sC; tl.sA = m.sA; tl.sB = m.sB;
+        const bool w_fold = m.sB == 1;
+        // plan rows per tile: 16 rows of a width fold, 32 columns of a height fold (64-byte runs of x),
+        // fewer while the tile does not fit 64 KB of LDS
+        int TA = w_fold ? 16 : 32;
+        auto lds_bytes = [&](int ta) {
+            const long long pitch = (w_fold ? m.B : ta) + 2;  // elements; an odd number of dwords
+            return 2ll * m.C * (w_fold ? ta : m.B) * pitch;
+        };
+        while (TA > (w_fold ? 1 : 8) && lds_bytes(TA) > 65536) TA /= 2;
+        if (lds_bytes(TA) <= 65536 && (long long)s.N * ((m.A + TA - 1) / TA) < (1ll << 31)) {
+            tl.TA = TA;
+            tl.tiles_a = (m.A + TA - 1) / TA;
+            const int pitch = (w_fold ? m.B : TA) + 2;
+            if (w_fold) { tl.R = TA; tl.L = m.B; tl.la = pitch; tl.lb = 1; tl.LC = TA * pitch; }
+            else { tl.R = m.B; tl.L = TA; tl.la = 1; tl.lb = pitch; tl.LC = m.B * pitch; }
+            nchw_to_fold_tile_kernel<<<(unsigned)(s.N * tl.tiles_a), kThreads, (size_t)lds_bytes(TA), st>>>(
+                (const uint16_t *)x, (uint16_t *)x_fold, tl);
+            return last_error();
+        }
+    }
     const int vec = ((uintptr_t)x_fold % 16 == 0) ? 1 : 0;
     const long long pieces = (m.total * s.elem_bytes + 15) / 16;
     const unsigned grid = blocks_for(pieces, kThreads, 1 << 22);
