@@ -34,7 +34,9 @@ def axis_code(fc, axis):
 
 
 # N, C, H, W, F (F divides the folded axis in both orientations)
-FOLD_CASES = [(2, 3, 16, 32, 8), (1, 1, 64, 32, 32), (3, 5, 8, 12, 4), (1, 2, 6, 6, 2), (2, 12, 28, 20, 4), (1, 7, 5, 5, 1)]
+FOLD_CASES = [(2, 3, 16, 32, 8), (1, 1, 64, 32, 32), (3, 5, 8, 12, 4), (1, 2, 6, 6, 2), (2, 12, 28, 20, 4), (1, 7, 5, 5, 1),
+              # the LDS-tiled pass: a ragged last tile on either axis; rows so long that the tile height shrinks
+              (2, 3, 40, 72, 8), (1, 12, 24, 224, 4)]
 
 
 @pytest.mark.parametrize("dt", ["f16", "f32"])
