@@ -97,6 +97,25 @@ def test_store_pacing_changes_nothing(env):
         L.forward(xd, y_free, flags=fc.FLAG_UNPACED)
     torch.cuda.synchronize()
     assert torch.equal(y_paced, y_free)
+    # a paced launch replayed from a captured graph (it reads the wall clock, no host state): every replay, with
+    # eager launches and synchronisations in between, writes the same bytes
+    y_graph = L.new_output()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        L.forward(xd, y_graph)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        L.forward(xd, y_graph)
+    for _ in range(3):
+        y_graph.fill_(float("nan"))
+        gr.replay()
+        L.forward(xd, y_free, flags=fc.FLAG_UNPACED)
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_paced)
+    del gr, y_graph
     for _ in range(3):
         L.forward_padded(xd, y_free)
     s = L.plan.shapes
