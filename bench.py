@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16/bf16
 KERNEL_NAMES = ["gather", "tiled", "stream"]
-EXTRAS = ["dense_k", "padded", "pacing", "repack", "compact_filter", "copies", "c5_stack", "small_configs", "gemm_1x1", "nchw",
+EXTRAS = ["dense_k", "padded", "pacing", "repack", "compact_filter", "copies", "c5_stack", "small_configs", "gemm_1x1", "fp32", "nchw",
           "fold_choice", "operand_values"]
 
 
@@ -447,6 +447,24 @@ def main():
                               "GBps": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9,
                               "frac_of_hbm_peak": (gs.x_bytes + gs.y_bytes) / (g_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del G, gxd, gy
+    if "fp32" in want:
+        # the headline layer in fp32 (the precision of the paper's appendix listing): the streaming kernel with
+        # steps of 8 K values as four MFMAs of K = 2; bound by the fp32 matrix rate, not by the 822 MB output
+        lf = wl.Layer(**{**layer.__dict__})
+        lf.dtype = "f32"
+        Lf = runner.FoldedLayer(lf, ws[0].float(), None if bs[0] is None else bs[0].float())
+        sf = Lf.plan.shapes
+        xfd = x.float().cuda()
+        yf = Lf.new_output()
+        _, f_ms = time_events(lambda: Lf.forward(xfd, yf), 30, 5)
+        _, fp_ms = time_events(lambda: Lf.forward_padded(xfd, yf), 10, 3)
+        extras["fp32"] = {"kernel": KERNEL_NAMES[sf.conv_kernel], "ms": f_ms, "padded_ms": fp_ms,
+                          "useful_tflops": sf.useful_flops / (f_ms * 1e-3) / 1e12,
+                          "issued_tflops": sf.issued_flops_band / (f_ms * 1e-3) / 1e12,
+                          "issued_pct_of_fp32_mfma_peak": 100.0 * sf.issued_flops_band / (f_ms * 1e-3) / 1e12 / 157.3,
+                          "GBps": (sf.x_bytes + sf.y_bytes) / (f_ms * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": (sf.x_bytes + sf.y_bytes) / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del Lf, xfd, yf
     if "nchw" in want:
         # the headline layer handed over channels-first (NCHW / OIHW): fold and reconstruct are real
         # re-indexing kernels here, the convolution between them is the same kernel as above

@@ -64,7 +64,10 @@ enum {
     FOLDCONV_FLAG_RELU = 1u,          /* y = max(0, conv + bias)                               */
     FOLDCONV_FLAG_DENSE_K = 2u,       /* walk every K-step of w', structural zeros included,
                                          instead of only the band that can be non-zero for the
-                                         output slots of a tile.  Same result for finite data. */
+                                         output slots of a tile.  Same result for finite data.
+                                         (An fp32 plan given the compact filter walks the band
+                                         where the dense walk would not fit the streaming kernel:
+                                         the off-band blocks do not exist in that storage.)    */
     FOLDCONV_FLAG_KEEP_FOLDED = 4u,   /* write y' [N][H_out][W'_out][F*C_out], not y           */
     FOLDCONV_FLAG_FILTER_PACKED = 8u, /* workspace already holds the packed filter written by a
                                          previous call with the same plan and the same filter

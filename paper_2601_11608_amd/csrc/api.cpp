@@ -73,7 +73,7 @@ extern "C" int foldconv_pack_filter(foldconv_plan_t plan, const void *w_exp, voi
     if (plan->s.conv_kernel == FC_KERNEL_GATHER) return FOLDCONV_OK;
     int st = check_ws(workspace, workspace_bytes, plan->s.workspace_bytes);
     if (st) return st;
-    if (!aligned(w_exp, 2)) return FOLDCONV_ERR_BADARG;
+    if (!aligned(w_exp, (size_t)plan->s.elem_bytes)) return FOLDCONV_ERR_BADARG;
     st = hip_status(fc_launch_pack(plan->fold, plan->s.elem_bytes, w_exp, workspace, stream));
     if (st == FOLDCONV_OK) fc_stamp(&plan->packed_ws, workspace);
     return st;
@@ -132,6 +132,13 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
         if (!fc_stamped(&plan->compact_ws, workspace)) return FOLDCONV_ERR_WORKSPACE;  // never packed by this plan
         if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
         g.compact = 1;
+        if (kernel == FC_KERNEL_STREAM && s.dtype == FOLDCONV_F32) {
+            // An fp32 dense walk too long for the streaming instances would run the element-gather kernel, which
+            // reads the canonical filter, not this chunked form.  The off-band blocks do not exist in compact
+            // storage anyway: walk the band (same result).
+            StreamShape sh;
+            if (!fc_stream_shape(g, g.band, &sh)) g.band = 1;
+        }
         if (out_nchw)
             return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, x_fold, workspace, bias, y, stream));
         return hip_status(

@@ -17,6 +17,11 @@
 //     that every store instruction writes whole rows of the reconstructed
 //     output: 16 bytes per lane, consecutive lanes on consecutive addresses.
 // Waves never synchronise with each other.
+// The element type is a template parameter.  Everything is laid out in 16-byte
+// chunks (8 elements of fp16/bf16, 4 of fp32), and a K-step is two chunks, one per
+// half of the wave: one 32x32x16 MFMA for the 16-bit types, four chained
+// 32x32x2 MFMAs for fp32 (whose K index inside the step is a permutation of the
+// chunk order, the same one for both operands, so the sum is unchanged).
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
@@ -85,9 +90,12 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                    const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
     using T = typename TR::T;
     using Vec = typename TR::Vec;
+    constexpr int EB = (int)sizeof(T);            // bytes per element
+    constexpr int E = 16 / EB;                    // elements per 16-byte chunk: 8 (16-bit types) or 4 (fp32);
+                                                  // a K-step is two chunks, one per half of the wave
     constexpr int COLS = 32 * NT;                 // output columns per wave
-    constexpr int PITCH = COLS * 2 + 16;          // bytes per LDS row (padded)
-    constexpr int CHUNKS = COLS / 8;              // 16-byte chunks per row
+    constexpr int PITCH = COLS * EB + 16;         // bytes per LDS row (padded)
+    constexpr int CHUNKS = COLS / E;              // 16-byte chunks per row
     constexpr int PASSES = (32 * CHUNKS + 63) / 64;
     constexpr int SLAB = 32 * PITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * SLAB];
@@ -110,9 +118,9 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     const int KS = EXACT ? KSM : a.ksteps;
     const int n_lo = ng * COLS;
     int e_lo, e_hi;
-    fc_band_window(g, n_lo, n_lo + COLS, 8, &e_lo, &e_hi);
-    const int q_per_kh = g.kwin / 8;
-    const int e0 = e_lo + 8 * hf;  // this lane's extended channel at K-step 0
+    fc_band_window(g, n_lo, n_lo + COLS, E, &e_lo, &e_hi);
+    const int q_per_kh = g.kwin / E;
+    const int e0 = e_lo + E * hf;  // this lane's extended channel at K-step 0
 
     // ---- filter fragments, resident for the kernel's lifetime -----------------
     Vec wf[KHM][KSM][NT];
@@ -122,12 +130,12 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int ks = 0; ks < KSM; ++ks)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int e = e0 + 16 * ks;
+                const int e = e0 + 2 * E * ks;
                 const int n = n_lo + 32 * nt + r;
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (kh < KH && ks < KS && e < e_hi && n < g.NCo) {
-                    const int q = (e - g.e_min) >> 3;
-                    const long long ci = g.compact ? fc_compact_chunk(g, kh, q, n)
+                    const int q = (e - g.e_min) >> (E == 8 ? 3 : 2);  // e >= e_min, both multiples of E
+                    const long long ci = g.compact ? fc_compact_chunk<E>(g, kh, q, n)
                                                    : ((long long)kh * q_per_kh + q) * g.NCo + n;
                     if (ci >= 0) v = wp[ci];  // off-band chunks of the compact form are zeros
                 }
@@ -136,12 +144,12 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     // bias enters as a rank-1 MFMA: A = bias in K slot 0, B = 1 in K slot 0
     Vec bf[NT], ones;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ones[i] = (T)0.0f;
+    for (int i = 0; i < E; ++i) ones[i] = (T)0.0f;
     if (hf == 0) ones[0] = (T)1.0f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) bf[nt][i] = (T)0.0f;
+        for (int i = 0; i < E; ++i) bf[nt][i] = (T)0.0f;
         const int n = n_lo + 32 * nt + r;
         if (g.has_bias && hf == 0 && n < g.NCo) bf[nt][0] = bias[n % g.Co];
     }
@@ -178,7 +186,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     unsigned ksmask = 0;
 #pragma unroll
     for (int ks = 0; ks < KSM; ++ks)
-        if (ks < KS && e0 + 16 * ks < e_hi) ksmask |= 1u << ks;
+        if (ks < KS && e0 + 2 * E * ks < e_hi) ksmask |= 1u << ks;
 
     // per-lane constants of the row-wise store phase: LDS byte offset of the lane's 16-byte
     // chunk in each pass and, when stored rows are contiguous (linear_out), its byte offset
@@ -190,10 +198,10 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         const int idx = p * 64 + lane;
         st_row[p] = idx / CHUNKS;
         const int ch = idx - st_row[p] * CHUNKS;
-        st_col[p] = n_lo + 8 * ch;  // first output column of the chunk
+        st_col[p] = n_lo + E * ch;  // first output column of the chunk
         const bool in = st_row[p] < 32 && st_col[p] < g.NCo;
         st_lds[p] = (in ? st_row[p] : 0) * PITCH + ch * 16;
-        st_lin[p] = in ? 2u * ((unsigned)st_row[p] * (unsigned)g.NCo + (unsigned)st_col[p]) : kOutOfRange;
+        st_lin[p] = in ? (unsigned)EB * ((unsigned)st_row[p] * (unsigned)g.NCo + (unsigned)st_col[p]) : kOutOfRange;
     }
     const unsigned long long y_rows_total = (unsigned long long)g.N * (unsigned)g.Hout;
 
@@ -215,7 +223,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         unsigned colok = 0;
 #pragma unroll
         for (int ks = 0; ks < KSM; ++ks) {
-            const int col = col0 + 16 * ks;
+            const int col = col0 + 2 * E * ks;
             if (((ksmask >> ks) & 1u) && col >= 0 && col < g.in_row) colok |= 1u << ks;
         }
 #pragma unroll
@@ -224,10 +232,10 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
             const bool rv = vm && kh < KH && hi >= 0 && hi < g.H;
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks) {
-                // in range: row hi exists and the 8-element chunk [col, col+8) lies inside it
-                // (col and in_row are multiples of 8)
+                // in range: row hi exists and the chunk [col, col+E) lies inside it
+                // (col and in_row are multiples of E)
                 const bool ok = rv && ((colok >> ks) & 1u);
-                const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRange;
+                const unsigned voff = ok ? (unsigned)EB * (unsigned)(pix0 + kh * g.in_row + 2 * E * ks) : kOutOfRange;
                 asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst[kh][ks]) : "v"(voff), "s"(xr) : "memory");
             }
         }
@@ -256,7 +264,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
 #pragma unroll
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
+        for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma_k0(bf[nt], ones, zero);
         if (!EXACT) {
             // Instances with run-time K guards drain every fragment load here, ahead of the guards:
             // a fragment whose K-step is guarded off is never waited for below, and its registers
@@ -296,15 +304,28 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                u32x2 pk = {pack2<TR>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2<TR>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
-                if (RELU) {
-                    // max(v, 0) on the rounded 16-bit patterns as signed integers: negative
-                    // values (sign bit set) become +0, everything else is unchanged
-                    typedef short s16x4 __attribute__((ext_vector_type(4)));
-                    const s16x4 z = {0, 0, 0, 0};
-                    pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
+                // four consecutive output columns of pixel r
+                unsigned char *dst = slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * EB;
+                if constexpr (EB == 2) {
+                    u32x2 pk = {pack2<TR>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2<TR>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
+                    if (RELU) {
+                        // max(v, 0) on the rounded 16-bit patterns as signed integers: negative
+                        // values (sign bit set) become +0, everything else is unchanged
+                        typedef short s16x4 __attribute__((ext_vector_type(4)));
+                        const s16x4 z = {0, 0, 0, 0};
+                        pk = __builtin_bit_cast(u32x2, __builtin_elementwise_max(__builtin_bit_cast(s16x4, pk), z));
+                    }
+                    *reinterpret_cast<u32x2 *>(dst) = pk;
+                } else {
+                    floatx4_t v = {acc[nt][4 * q], acc[nt][4 * q + 1], acc[nt][4 * q + 2], acc[nt][4 * q + 3]};
+                    if (RELU) {
+                        // the same rule on the fp32 patterns (a negative zero or a NaN with the sign bit set becomes +0)
+                        typedef int s32x4 __attribute__((ext_vector_type(4)));
+                        const s32x4 z = {0, 0, 0, 0};
+                        v = __builtin_bit_cast(floatx4_t, __builtin_elementwise_max(__builtin_bit_cast(s32x4, v), z));
+                    }
+                    *reinterpret_cast<floatx4_t *>(dst) = v;
                 }
-                *reinterpret_cast<u32x2 *>(slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * 2) = pk;
             }
         wave_lds_sync();
         if (a.pace) {  // wave-uniform, scalar instructions only; the spin is bounded whatever the clock reads
@@ -325,7 +346,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 base_el = (unsigned long long)cur_rowid0 * (unsigned)g.out_row;
                 left_el = (y_rows_total - cur_rowid0) * (unsigned)g.out_row;
             }
-            const unsigned long long left_b = left_el * 2ull;
+            const unsigned long long left_b = left_el * (unsigned long long)EB;
             const __amdgpu_buffer_rsrc_t yr = __builtin_amdgcn_make_buffer_rsrc(
                 y + base_el, 0, (int)(left_b > 0x7fffffffull ? 0x7fffffffull : left_b), 0x00020000);
 #pragma unroll
@@ -339,8 +360,8 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                     const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
                     const unsigned oc = (t - q * (unsigned)g.Wf_out) * (unsigned)g.NCo + (unsigned)st_col[p];
                     const bool ok = st_lin[p] != kOutOfRange && cur_m0 + (unsigned)st_row[p] < (unsigned)g.M &&
-                                    oc + 8u <= (unsigned)g.out_row;
-                    off = ok ? 2u * (q * (unsigned)g.out_row + oc) : kOutOfRange;
+                                    oc + (unsigned)E <= (unsigned)g.out_row;
+                    off = ok ? (unsigned)EB * (q * (unsigned)g.out_row + oc) : kOutOfRange;
                 }
                 __builtin_amdgcn_raw_buffer_store_b128(v, yr, off, 0, 2 /* nt */);
             }
@@ -355,6 +376,9 @@ template <typename TR, int NT, int KHM, int KSM, int OCC>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y,
                 hipStream_t st) {
     using T = typename TR::T;
+    // fp32 rows of 128 columns would need more LDS for the four waves' slabs than a workgroup may declare;
+    // fc_stream_shape never picks those instances for fp32
+    if constexpr (sizeof(T) == 4 && NT > 2) return (int)hipErrorInvalidValue; else {
     StreamArgs a;
     a.MT = (unsigned)((g.M + 31) / 32);
     a.NG = (g.NCo + 32 * NT - 1) / (32 * NT);
@@ -390,6 +414,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     else FC_GO(false, false);
 #undef FC_GO
     return (int)hipGetLastError();
+    }
 }
 
 template <typename TR>
@@ -412,5 +437,6 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
     hipStream_t st = (hipStream_t)stream;
     if (dt == FOLDCONV_F16) return launch_shape<F16Traits>(g, sh, x, w_pack, bias, y, st);
     if (dt == FOLDCONV_BF16) return launch_shape<BF16Traits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_F32) return launch_shape<F32ChunkTraits>(g, sh, x, w_pack, bias, y, st);
     return (int)hipErrorInvalidValue;
 }

@@ -101,7 +101,7 @@ conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__
         for (int nt = 0; nt < NT; ++nt) {
             const int kh = idx / KSM, q = 2 * (idx % KSM) + hf;
             const int n = n_lo + 32 * nt + r;
-            const long long ci = g.compact ? fc_compact_chunk(g, kh, q, n) : ((long long)kh * QM + q) * g.NCo + n;
+            const long long ci = g.compact ? fc_compact_chunk<8>(g, kh, q, n) : ((long long)kh * QM + q) * g.NCo + n;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (ci >= 0) v = wp[ci];  // structural zeros of the compact form
             wf[idx][nt] = __builtin_bit_cast(Vec, v);

@@ -117,7 +117,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 u32x4 v = {0u, 0u, 0u, 0u};
                 if (kh < KH && ks < KS && e < e_hi) {
                     const int q = (e - g.e_min) >> 3;
-                    const long long ci = g.compact ? fc_compact_chunk(g, kh, q, n)
+                    const long long ci = g.compact ? fc_compact_chunk<8>(g, kh, q, n)
                                                    : ((long long)kh * q_per_kh + q) * g.NCo + n;
                     if (ci >= 0) v = wp[ci];  // off-band chunks of the compact form are zeros
                 }

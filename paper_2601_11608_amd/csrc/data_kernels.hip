@@ -140,18 +140,20 @@ pad_filter_kernel(const U *__restrict__ w, U *__restrict__ wp, int taps, int C, 
 // so that one lane's eight consecutive K values of one output column are a
 // single 16-byte load.
 // ---------------------------------------------------------------------------
+template <typename U>  // uint16_t: chunks of 8 rows; uint32_t (fp32): chunks of 4
 __global__ void __launch_bounds__(kThreads)
-pack_filter_kernel(const uint16_t *__restrict__ we, u32x4 *__restrict__ pack, int KH, int kwin, int NCo) {
-    const int q_per_kh = kwin / 8;
+pack_filter_kernel(const U *__restrict__ we, u32x4 *__restrict__ pack, int KH, int kwin, int NCo) {
+    constexpr int E = 16 / sizeof(U);
+    const int q_per_kh = kwin / E;
     const long long total = (long long)KH * q_per_kh * NCo;
     const long long stride = (long long)gridDim.x * kThreads;
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
         int n = (int)(i % NCo);
-        long long r = i / NCo;  // kh*q_per_kh + q  ==  first filter row / 8
-        const uint16_t *srcp = we + (r * 8) * NCo + n;
-        uint16_t v[8];
+        long long r = i / NCo;  // kh*q_per_kh + q  ==  first filter row / E
+        const U *srcp = we + (r * E) * NCo + n;
+        U v[E];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = srcp[(long long)j * NCo];
+        for (int j = 0; j < E; ++j) v[j] = srcp[(long long)j * NCo];
         u32x4 out;
         __builtin_memcpy(&out, v, 16);
         pack[i] = out;
@@ -164,9 +166,11 @@ pack_filter_kernel(const uint16_t *__restrict__ we, u32x4 *__restrict__ pack, in
 // blocks of the expanded filter exist in this form
 // (paper: "Potential Optimizations for Sparsity", storing just the non-zero blocks).
 // ---------------------------------------------------------------------------
+template <typename U>  // uint16_t: chunks of 8 rows; uint32_t (fp32): chunks of 4
 __global__ void __launch_bounds__(kThreads)
-compact_filter_kernel(const uint16_t *__restrict__ w, u32x4 *__restrict__ cpk, int KH, int taps_c /* KW*C_in */,
+compact_filter_kernel(const U *__restrict__ w, u32x4 *__restrict__ cpk, int KH, int taps_c /* KW*C_in */,
                       int Co, int cJ, int cgcd, long long total) {
+    constexpr int E = 16 / sizeof(U);
     const long long stride = (long long)gridDim.x * kThreads;
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
         const int co = (int)(i % Co);
@@ -175,11 +179,11 @@ compact_filter_kernel(const uint16_t *__restrict__ w, u32x4 *__restrict__ cpk, i
         r /= cJ;
         const int kh = (int)(r % KH);
         const int ph = (int)(r / KH);
-        uint16_t v[8];
+        U v[E];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int t = 8 * j + e - ph * cgcd;  // row of the kh-th KW*C_in x C_out tap matrix
-            v[e] = (t >= 0 && t < taps_c) ? w[((long long)kh * taps_c + t) * Co + co] : (uint16_t)0;
+        for (int e = 0; e < E; ++e) {
+            const int t = E * j + e - ph * cgcd;  // row of the kh-th KW*C_in x C_out tap matrix
+            v[e] = (t >= 0 && t < taps_c) ? w[((long long)kh * taps_c + t) * Co + co] : (U)0;
         }
         u32x4 out;
         __builtin_memcpy(&out, v, 16);
@@ -521,21 +525,28 @@ int fc_launch_crop_channels(const foldconv_plan_s *p, const void *y_pad, void *y
 }
 
 int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream) {
-    if (elem_bytes != 2 || g.kwin % 8 != 0) return (int)hipErrorInvalidValue;
+    if (elem_bytes * g.epc != 16 || g.kwin % g.epc != 0) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    const long long total = (long long)g.KH * (g.kwin / 8) * g.NCo;
+    const long long total = (long long)g.KH * (g.kwin / g.epc) * g.NCo;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
-    pack_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    if (elem_bytes == 2)
+        pack_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    else
+        pack_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
     return last_error();
 }
 
 int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_compact, void *stream) {
-    if (elem_bytes != 2 || g.FC % 8 != 0) return (int)hipErrorInvalidValue;
+    if (elem_bytes * g.epc != 16 || g.FC % g.epc != 0) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const long long total = (long long)fc_compact_phases(g) * g.KH * g.cJ * g.Co;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
-    compact_filter_kernel<<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH, g.KW * g.C, g.Co,
-                                                     g.cJ, g.cgcd, total);
+    if (elem_bytes == 2)
+        compact_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH,
+                                                                   g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
+    else
+        compact_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (u32x4 *)w_compact, g.KH,
+                                                                   g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
     return last_error();
 }
 

@@ -32,6 +32,7 @@ struct ConvGeom {
     int Co;      // bias period (C_out)
     int C;       // original input channels (band arithmetic)
     int F, KH, KW, pad_h, pad_w;
+    int epc;     // elements per 16-byte chunk: 8 for the 16-bit types, 4 for fp32
     int e_min, e_max;  // dense window of extended channels, [e_min, e_max)
     int kwin;          // e_max - e_min = KW'*FC = filter rows per kh
     int in_row;        // elements per input row  (Wf*FC)
@@ -63,24 +64,29 @@ FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int 
     *e_hi = hi;
 }
 
-// Compact storage of the expanded filter for the 16-bit vector kernels.  Every output slot g
+// Compact storage of the expanded filter for the vector kernels.  Every output slot g
 // uses the same KW*C_in x C_out matrix per kh (the non-zero blocks of w' are copies of the original
 // taps; paper: "Potential Optimizations for Sparsity": keep only the non-zero blocks); slots differ
 // only in where that matrix starts, a = (g-p)*C_in - e_min rows into the window.  In 16-byte
-// chunks of 8 rows the start falls on phase a mod 8, a multiple of gcd(C_in, 8), so one
-// zero-padded copy per phase serves every slot:
-//   cpk[ph][kh][j][co][i] = w[kh][t / C_in][t % C_in][co],  t = 8*j + i - ph*gcd,  0 <= t < KW*C_in, else 0.
-// Returns the chunk of cpk that equals rows [e_min+8q, e_min+8q+8) of column n of w', or -1 when
+// chunks of E = epc rows (8 for the 16-bit types, 4 for fp32) the start falls on phase a mod E, a multiple of
+// gcd(C_in, E), so one zero-padded copy per phase serves every slot:
+//   cpk[ph][kh][j][co][i] = w[kh][t / C_in][t % C_in][co],  t = E*j + i - ph*gcd,  0 <= t < KW*C_in, else 0.
+// Returns the chunk of cpk that equals rows [e_min+E*q, e_min+E*q+E) of column n of w', or -1 when
 // those rows are structural zeros.
+// E is a template argument (it must equal g.epc) so that the kernels divide by shifting.
+template <int E>
 FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
+    static_assert(E == 4 || E == 8, "16-byte chunks of a 32-bit or a 16-bit type");
+    constexpr int SH = E == 8 ? 3 : 2;
     const int slot = n / g.Co, co = n - slot * g.Co;
     const int a = (slot - g.pad_w) * g.C - g.e_min;  // >= 0 because e_min <= -p*C_in
-    const int j = q - (a >> 3);
+    const int j = q - (a >> SH);
     if (j < 0 || j >= g.cJ) return -1;
-    return ((long long)(((a & 7) / g.cgcd) * g.KH + kh) * g.cJ + j) * g.Co + co;
+    return ((long long)(((a & (E - 1)) / g.cgcd) * g.KH + kh) * g.cJ + j) * g.Co + co;
 }
-FC_HD int fc_gcd8(int c) { return (c % 8 == 0) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
-FC_HD int fc_compact_phases(const ConvGeom &g) { return 8 / g.cgcd; }
+// gcd(c, epc) for epc = 4 or 8
+FC_HD int fc_gcd_chunk(int c, int epc) { return (c % 8 == 0 && epc == 8) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
+FC_HD int fc_compact_phases(const ConvGeom &g) { return g.epc / g.cgcd; }
 
 // How the persistent streaming kernels deal their 32-pixel M tiles to the XCDs (8 on MI355X; workgroup
 // b runs on XCD b % parts, each XCD has its own L2).  Tiles go out in chunks of CH consecutive tiles, chunk c

@@ -5,7 +5,8 @@
 // the folded input, columns = output pixels m.  Per lane l of the wave64:
 //   16-bit types, v_mfma_f32_32x32x16_{f16,bf16}: A = w'[k0 + 8*(l/32) + j][n0 + l%32],
 //     B = A_im2col[m0 + l%32][k0 + 8*(l/32) + j], j = 0..7 (both K-contiguous);
-//   fp32, v_mfma_f32_32x32x2_f32: one element each, k = k0 + l/32.
+//   fp32, v_mfma_f32_32x32x2_f32: one element each, k = k0 + l/32 (the element-gather kernel), or
+//     four per lane used by four MFMAs in turn (F32ChunkTraits, the streaming kernel).
 // Accumulator register r (0..15) of lane l holds
 //   D[n0 + 8*(r/4) + 4*(l/32) + r%4][m0 + l%32],
 // i.e. four consecutive output channels of one pixel per register quad.
@@ -26,6 +27,8 @@ struct F16Traits {
     static __device__ __forceinline__ floatx16_t mfma(Vec a, Vec b, floatx16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
+    // the product when only element 0 of a and b is non-zero (the rank-1 bias term)
+    static __device__ __forceinline__ floatx16_t mfma_k0(Vec a, Vec b, floatx16_t c) { return mfma(a, b, c); }
     static __device__ __forceinline__ T from_float(float v) { return (T)v; }
 };
 
@@ -37,7 +40,28 @@ struct BF16Traits {
     static __device__ __forceinline__ floatx16_t mfma(Vec a, Vec b, floatx16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
+    static __device__ __forceinline__ floatx16_t mfma_k0(Vec a, Vec b, floatx16_t c) { return mfma(a, b, c); }
     static __device__ __forceinline__ T from_float(float v) { return (T)v; }  // v_cvt_pk_bf16_f32: round to nearest even
+};
+
+// fp32 in 16-byte chunks, for the kernels that read four K-contiguous elements per lane: one K-step of 8 is
+// four v_mfma_f32_32x32x2_f32, the j-th on element j of both operands (lane l: k = k0 + 4*(l/32) + j).
+struct F32ChunkTraits {
+    using T = float;
+    using Vec = floatx4_t;
+    static constexpr int kPerLane = 4;
+    static constexpr int kStep = 8;
+    static __device__ __forceinline__ floatx16_t mfma(Vec a, Vec b, floatx16_t c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
+    }
+    // the product when only element 0 of a and b is non-zero (the rank-1 bias term): one MFMA instead of four
+    static __device__ __forceinline__ floatx16_t mfma_k0(Vec a, Vec b, floatx16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ T from_float(float v) { return v; }
 };
 
 struct F32Traits {

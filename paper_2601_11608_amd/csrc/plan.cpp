@@ -45,13 +45,19 @@ static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int alig
 // fits, else on the largest streaming instance, else on the tiled kernel).
 static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t dtype) {
     g.band = band;
-    const int kstep = dtype == FOLDCONV_F32 ? 2 : 16;
+    const bool f32 = dtype == FOLDCONV_F32;
     const int align = fc_band_align(plan_kernel, dtype);
-    if (plan_kernel == FC_KERNEL_GATHER) return issued_flops(g, band, 32, kstep, align, false, 0);
+    if (plan_kernel == FC_KERNEL_GATHER) return issued_flops(g, band, 32, f32 ? 2 : 16, 1, false, 0);
+    // the vector kernels walk K in steps of two 16-byte chunks: 16 elements of a 16-bit type, 8 of fp32
+    // (there as four MFMAs of K = 2)
+    const int kstep = f32 ? 8 : 16;
     if (plan_kernel == FC_KERNEL_STREAM) {
         StreamShape sh;
         if (!band && fc_stream_lds_ok(g)) return issued_flops(g, 0, 64, kstep, align, false, 0);  // bias added in fp32
-        if (fc_stream_shape(g, band, &sh)) return issued_flops(g, band, 32 * sh.nt, kstep, align, false, 16);
+        // the rank-1 bias product: one 16-wide MFMA, or one of K = 2 for fp32
+        if (fc_stream_shape(g, band, &sh)) return issued_flops(g, band, 32 * sh.nt, kstep, align, false, f32 ? 2 : 16);
+        // fp32 has no tiled kernel: a dense walk too long for the streaming instances runs the gather kernel
+        if (f32) return issued_flops(g, band, 32, 2, 1, false, 0);
     }
     return issued_flops(g, band, fc_tiled_bn(g), kstep, align, true, 16);
 }
@@ -80,7 +86,7 @@ static double model_seconds(const foldconv_shapes_t &s, int wave_columns) {
     double overhead, rate, y_eff = y;
     if (s.conv_kernel == FC_KERNEL_STREAM) {
         overhead = 4.5e-6;
-        rate = 1.0e15;
+        rate = s.dtype == FOLDCONV_F32 ? 0.08e15 : 1.0e15;  // fp32: K = 2 MFMAs, 157 TFLOP/s peak
         const double cols = (double)((s.Co_fold + wave_columns - 1) / wave_columns) * wave_columns;
         y_eff = y * cols / (double)s.Co_fold;
     } else if (s.conv_kernel == FC_KERNEL_TILED) {
@@ -165,8 +171,9 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     g.pad_h = pad_h; g.pad_w = pad_w;
     g.e_min = (int)(d_min * FC); g.e_max = (int)((d_max + 1) * FC); g.kwin = g.e_max - g.e_min;
     g.in_row = (int)(Wf * FC); g.out_row = (int)(W_out * C_out); g.M = M;
-    g.cgcd = fc_gcd8(C_in);
-    g.cJ = (8 - g.cgcd + KW * C_in + 7) / 8;
+    g.epc = 16 / eb;
+    g.cgcd = fc_gcd_chunk(C_in, g.epc);
+    g.cJ = (g.epc - g.cgcd + KW * C_in + g.epc - 1) / g.epc;
 
     // Zero-padded reference problem: F = 1, every pixel C_pad channels.
     ConvGeom &q = p->padc;
@@ -175,7 +182,8 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     q.pad_h = pad_h; q.pad_w = pad_w;
     q.e_min = -pad_w * C_pad; q.e_max = (KW - pad_w) * C_pad; q.kwin = q.e_max - q.e_min;
     q.in_row = W * C_pad; q.out_row = (int)(W_out * Co_pad); q.M = M_pad;
-    q.cgcd = 8; q.cJ = KW * C_pad / 8;
+    q.epc = 16 / eb;
+    q.cgcd = q.epc; q.cJ = KW * C_pad / q.epc;
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
     if (W_out != Wf_out * F) {

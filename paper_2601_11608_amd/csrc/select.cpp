@@ -14,27 +14,32 @@ int max_ksteps(ConvGeom g, int band, int cols) {
     int worst = 0;
     for (int n0 = 0; n0 < g.NCo; n0 += cols) {
         int e_lo, e_hi;
-        fc_band_window(g, n0, n0 + cols, 8, &e_lo, &e_hi);
-        int k = (e_hi - e_lo + 15) / 16;
+        fc_band_window(g, n0, n0 + cols, g.epc, &e_lo, &e_hi);
+        int k = (e_hi - e_lo + 2 * g.epc - 1) / (2 * g.epc);  // K-steps of two chunks
         if (k > worst) worst = k;
     }
     return worst;
 }
 }  // namespace
 
-// Conditions shared by the two vector kernels.
+// Conditions shared by the vector kernels.
 static bool vector_ok(const ConvGeom &g) {
-    // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of 8.
-    if (g.FC % 8 != 0 || g.NCo % 8 != 0 || g.out_row % 8 != 0 || g.kwin % 8 != 0) return false;
-    // 32-bit byte offsets into x and into the packed filter, 32-bit (offset / 8) into y.
+    // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of a chunk
+    // (8 elements of a 16-bit type, 4 of fp32).
+    const int E = g.epc;
+    if (E != 8 && E != 4) return false;
+    if (g.FC % E != 0 || g.NCo % E != 0 || g.out_row % E != 0 || g.kwin % E != 0) return false;
+    // 32-bit byte offsets into x and into the packed filter, 32-bit chunk index into y.
+    const long long eb = 16 / E;
     const long long x_elems = (long long)g.N * g.H * g.in_row;
     const long long y_elems = (long long)g.N * g.Hout * g.out_row;
     const long long w_elems = (long long)g.KH * g.kwin * g.NCo;
-    if (x_elems + 4LL * g.in_row >= (1LL << 30) || y_elems / 8 >= (1LL << 32) || w_elems >= (1LL << 30)) return false;
+    if ((x_elems + 4LL * g.in_row) * eb >= (1LL << 31) || y_elems / E >= (1LL << 32) || w_elems * eb >= (1LL << 31)) return false;
     return true;
 }
 
-bool fc_tiled_ok(const ConvGeom &g) { return vector_ok(g); }
+// the LDS-tiled kernel and the two variants of the streaming kernel below exist for the 16-bit types only
+bool fc_tiled_ok(const ConvGeom &g) { return g.epc == 8 && vector_ok(g); }
 
 int fc_tiled_bn(const ConvGeom &g) {
     // Multiplies issued by a tile width = sum over its N tiles of (K blocks inside the tile's band
@@ -63,16 +68,18 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     // exact multiply-high division of (tile start + lane) by the folded width and by the output height
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
-    if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
+    if (34LL * g.out_row * (16 / g.epc) >= (1LL << 31) || 34LL * g.NCo * (16 / g.epc) >= (1LL << 31)) return false;
     // 64 columns per wave first: for the small-C_in layers this is one K-step per kh with the
     // fewest structural-zero products; wider waves only when no such instance fits.
     static const int prefer[] = {2, 4};
     for (int nt : prefer) {
+        if (g.epc == 4 && nt > 2) continue;  // fp32: 64 columns per wave only (LDS for the waves' output slabs)
         const int ks = max_ksteps(g, band, 32 * nt);
         // Beyond a dozen K-steps per tile the layer is bound by the matrix cores, not by the
         // output stream, and the LDS-tiled kernel (operands shared by four waves) is the better
         // tool.  The dense walk of a small-K layer may still use the largest instance.
-        if (band && g.KH * ks > 12) continue;
+        // (fp32 has no tiled kernel: any instance that fits is better than the element-gather kernel.)
+        if (band && g.epc == 8 && g.KH * ks > 12) continue;
         for (int i = 0; i < kNumInst; ++i)
             if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
                 out->inst = i;
@@ -85,7 +92,7 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
 }
 
 bool fc_stream_lds_ok(const ConvGeom &g) {
-    if (!vector_ok(g)) return false;
+    if (g.epc != 8 || !vector_ok(g)) return false;
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
     if (g.M >= (1LL << 31) - (1LL << 20)) return false;
@@ -101,7 +108,7 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
     // g.out_row is the plan's unfolded W_out here: elements per channel row of y for a width fold, rows per
     // channel plane for a height fold (the plan is the transposed image's).
     // one wave per 64 columns, at most 16 waves, 4 channels per LDS read
-    if (g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
+    if (g.epc != 8 || g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
     if (g.NCo % 64 != 0 || g.NCo > 1024) return false;
     if (height_fold) {
         // 16-byte pieces run along the image width = the plan's rows: whole pieces of 8 columns; a thread of the
@@ -126,10 +133,10 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
 }
 
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt) {
-    // fp32 and channel counts that miss the 16-byte chunk alignment run the
-    // element-gather MFMA kernel (the analogue of Algorithm 1's fallback: it is
-    // correct for every shape, just not fast).
-    if (dt == FOLDCONV_F32) return FC_KERNEL_GATHER;
+    // Channel counts that miss the 16-byte chunk alignment, and fp32 layers too large for the
+    // streaming kernel's registers, run the element-gather MFMA kernel (the analogue of
+    // Algorithm 1's fallback: it is correct for every shape, just not fast).
+    (void)dt;  // the element size is in g.epc
     StreamShape sh;
     if (fc_stream_shape(g, 1, &sh)) return FC_KERNEL_STREAM;
     if (fc_tiled_ok(g)) return FC_KERNEL_TILED;
@@ -147,5 +154,5 @@ int fc_band_tile_n(int kernel, const ConvGeom &g) {
 
 int fc_band_align(int kernel, foldconv_dtype_t dt) {
     if (kernel == FC_KERNEL_GATHER) return 1;
-    return dt == FOLDCONV_F32 ? 1 : 8;
+    return dt == FOLDCONV_F32 ? 4 : 8;
 }

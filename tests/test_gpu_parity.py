@@ -184,6 +184,13 @@ def test_forward_compact_filter(fc, oracle, case, dt):
     for extra in (0, fc.FLAG_DENSE_K, fc.FLAG_KEEP_FOLDED):
         y_c = run_compact(fc, plan, x, w, b, rflag | extra)
         y_p = run_folded(fc, plan, x, w, b, rflag | extra)
+        if dt == "f32" and extra == fc.FLAG_DENSE_K and not np.array_equal(bits(y_c), bits(y_p)):
+            # fp32 has no tiled kernel: a dense walk of the packed filter too long for the streaming
+            # instances runs the element-gather kernel, while the compact form walks the band on the
+            # streaming kernel: another summation order, the same result within the rounding bound
+            assert_elementwise(f64(y_c), ref, abs_sum(oracle, x, w, b, ph, pw), KH * KW * C, dt, "compact dense")
+            assert_elementwise(f64(y_p), ref, abs_sum(oracle, x, w, b, ph, pw), KH * KW * C, dt, "packed dense")
+            continue
         assert np.array_equal(bits(y_c), bits(y_p)), extra
         if not extra:
             assert rel_l2_per_image(f64(y_c), ref) <= TOL[dt]
@@ -366,7 +373,7 @@ def _random_cases(n, seed):
     return out
 
 
-@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("chunk", range(6))
 def test_random_geometries(fc, oracle, chunk, dt):
     kernels = set()
@@ -392,6 +399,41 @@ def test_random_geometries(fc, oracle, chunk, dt):
             assert err <= TOL[dt], (case, name, err)
             assert_elementwise(f64(y), ref, S, K, dt, "%s %s" % (case, name))
     assert len(kernels) >= 2
+
+
+@pytest.mark.parametrize("case", [(4, 64, 224, 3, 64, 3, 3, 1, 16, True, False),     # the headline layer's shape, 4 images
+                                  (2, 40, 48, 12, 48, 3, 3, 1, 4, False, True),       # c3-like: several K-steps per kh
+                                  (3, 1, 4000, 1, 64, 1, 9, 4, 32, True, False),      # 1-D, one input channel
+                                  (1, 30, 64, 6, 10, 3, 3, 1, 2, True, True)],        # F*C_out = 20: cropped columns
+                         ids=lambda c: "x".join(map(str, c[:9])))
+def test_fp32_layers_on_the_streaming_kernel(fc, oracle, case):
+    """fp32 tensors whose folded pixels are whole 16-byte chunks (F*C_in a multiple of 4) run the
+    streaming kernel: steps of 8 K values as four MFMAs of K = 2, fp32 all the way (paper, appendix
+    listing: the fp32 setting of its equivalence check).  Every walk and the zero-padded reference
+    against the oracle, rel-L2 and element by element."""
+    N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
+    dt = "f32"
+    x = draw((N, H, W, C), dt, 71)
+    w = (draw((KH, KW, C, Co), dt, 72) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+    b = draw((Co,), dt, 73) if hb else None
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    ref = oracle.conv_direct(f64(x), f64(w), None if b is None else f64(b), ph, pw, relu)
+    plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, x.dtype)
+    assert plan.shapes.conv_kernel == 2 and plan.shapes.workspace_bytes >= plan.shapes.w_exp_bytes
+    rflag = fc.FLAG_RELU if relu else 0
+    S, K = abs_sum(oracle, x, w, b, ph, pw), KH * KW * C
+    y_band = run_folded(fc, plan, x, w, b, rflag)
+    for name, y in (("band", y_band),
+                    ("dense", run_folded(fc, plan, x, w, b, rflag | fc.FLAG_DENSE_K)),
+                    ("compact", run_compact(fc, plan, x, w, b, rflag)),
+                    ("padded", run_padded(fc, plan, x, w, b, rflag))):
+        assert not bool(torch.isnan(y).any()), (case, name)
+        err = rel_l2_per_image(f64(y), ref)
+        print("fp32 %s %s: rel-L2 %.2e" % (case[:9], name, err), flush=True)
+        assert err <= TOL[dt], (case, name, err)
+        assert_elementwise(f64(y), ref, S, K, dt, "%s %s" % (case, name))
+    # the compact filter feeds the same values to the same MFMA slots as the packed one
+    assert np.array_equal(bits(run_compact(fc, plan, x, w, b, rflag)), bits(y_band))
 
 
 @pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])

@@ -172,7 +172,7 @@ def test_fused_channels_first_output_is_reported_in_the_plan(fc):
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16) == 1                      # the headline layer
     assert fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes.out_nchw_fused == 1
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.bfloat16) == 1
-    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.float32) == 0    # fp32 runs the gather kernel
+    assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, dt=torch.float32) == 0    # 16-bit types only
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 1      # height fold: pieces run across the plan's rows
     assert fused(64, 3, 224, 220, 64, 3, 3, 1, 16, axis=fc.FOLD_H) == 0      # ... which needs W_out in multiples of 8
     assert fused(64, 3, 224, 224, 64, 3, 3, 1, 4) == 0                       # F not a multiple of 8
@@ -238,8 +238,11 @@ def test_compact_filter_size(fc):
             assert s.filter_compact_bytes < s.w_exp_bytes / 3
     s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
     assert (s.w_exp_bytes, s.filter_compact_bytes) == (884736, 49152)
-    # the gather kernel (fp32, or channels off the chunk alignment) reads the original filter itself
+    # fp32 on the streaming kernel: chunks of 4 rows, 4/gcd(C_in,4) copies
     s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 8, "float32").shapes
+    assert s.conv_kernel == 2 and s.filter_compact_bytes == (4 * 3 * ((4 - 1 + 9 + 3) // 4) * 16 * 16 + 255) // 256 * 256
+    # the gather kernel (channels off the chunk alignment) reads the original filter itself
+    s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 1, "float32").shapes
     assert s.conv_kernel == 0 and s.filter_compact_bytes == (s.w_bytes + 255) // 256 * 256
 
 

@@ -60,7 +60,8 @@ def test_hand_counted_waits_cover_every_fragment(asm):
     for name in names:
         m = re.search(r"TraitsLi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb([01])ELb([01])E", name)
         nt, khm, ksm, exact = int(m.group(1)), int(m.group(2)), int(m.group(3)), m.group(5) == "1"
-        passes = 2 * nt                      # 16-byte store passes per 32-row tile of 32*nt columns
+        # 16-byte store passes per 32-row tile of 32*nt columns: 8 elements per piece, 4 for fp32
+        passes = (4 if "F32ChunkTraits" in name else 2) * nt
         lines = loop_lines(asm, name)
         loads = [i for i, l in enumerate(lines) if l.startswith("buffer_load_dwordx4")]
         assert len(loads) == khm * ksm, name
