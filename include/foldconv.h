@@ -188,7 +188,8 @@ FOLDCONV_API int foldconv_plan_nchw(int N, int C_in, int H, int W, int C_out, in
  * Fold-factor choice: among the power-of-two factors F <= 64 that divide W,
  * the one with the smallest estimated time max(HBM bytes / sustained HBM rate,
  * issued MFMA flops / sustained MFMA rate), where a factor that leaves F*C_in
- * off the 16-byte chunk alignment is charged the element-gather kernel's
+ * off the chunk alignment (a multiple of 4 elements; 8 for the full rate of
+ * the 16-bit kernels) is charged the element-gather kernel's
  * rate; ties go to the smaller F.  *fold_factor receives the choice (1 = do not fold).
  * paper: "F is chosen to align with Tensor core tile sizes"; the "lightweight
  * cost model ... channel size, tensor core tile alignment, and arithmetic

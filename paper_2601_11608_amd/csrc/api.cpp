@@ -132,10 +132,11 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
         if (!fc_stamped(&plan->compact_ws, workspace)) return FOLDCONV_ERR_WORKSPACE;  // never packed by this plan
         if (kernel != FC_KERNEL_GATHER && (!aligned(x_fold, 16) || !aligned(y, 16))) return FOLDCONV_ERR_BADARG;
         g.compact = 1;
-        if (kernel == FC_KERNEL_STREAM && s.dtype == FOLDCONV_F32) {
-            // An fp32 dense walk too long for the streaming instances would run the element-gather kernel, which
-            // reads the canonical filter, not this chunked form.  The off-band blocks do not exist in compact
-            // storage anyway: walk the band (same result).
+        if (kernel == FC_KERNEL_STREAM && !fc_tiled_ok(g)) {
+            // Where the tiled kernel does not serve the layer (fp32, 8-byte operand chunks), a dense walk too long
+            // for the streaming instances would run the element-gather kernel, which reads the canonical filter,
+            // not this chunked form.  The off-band blocks do not exist in compact storage anyway: walk the band
+            // (same result).
             StreamShape sh;
             if (!fc_stream_shape(g, g.band, &sh)) g.band = 1;
         }

@@ -12,8 +12,8 @@ int fc_launch_conv(int kernel, foldconv_dtype_t dt, const ConvGeom &g, const voi
             // tile among four waves through LDS.
             if (!g.band && fc_stream_lds_ok(g)) return fc_launch_conv_stream_lds(dt, g, x, w_pack, bias, y, stream);
             if (fc_stream_shape(g, g.band, &sh)) return fc_launch_conv_stream(dt, g, x, w_pack, bias, y, stream);
-            // fp32 has no tiled kernel; the element-gather kernel reads the canonical filter
-            if (dt == FOLDCONV_F32) return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);
+            // fp32 and 8-byte operand chunks have no tiled kernel; the element-gather kernel reads the canonical filter
+            if (!fc_tiled_ok(g)) return fc_launch_conv_gather(dt, g, x, w_exp, bias, y, stream);
             return fc_launch_conv_tiled(dt, g, x, w_pack, bias, y, stream);
         }
         case FC_KERNEL_TILED:

@@ -17,11 +17,13 @@
 //     that every store instruction writes whole rows of the reconstructed
 //     output: 16 bytes per lane, consecutive lanes on consecutive addresses.
 // Waves never synchronise with each other.
-// The element type is a template parameter.  Everything is laid out in 16-byte
-// chunks (8 elements of fp16/bf16, 4 of fp32), and a K-step is two chunks, one per
-// half of the wave: one 32x32x16 MFMA for the 16-bit types, four chained
-// 32x32x2 MFMAs for fp32 (whose K index inside the step is a permutation of the
-// chunk order, the same one for both operands, so the sum is unchanged).
+// The element type and the operand chunk are template parameters (the MFMA traits).
+// Both operands are read in chunks of E K-contiguous elements, and a K-step is two
+// chunks, one per half of the wave: 16-byte chunks and one 32x32x16 MFMA for the
+// 16-bit types; 8-byte chunks and one 32x32x8 MFMA for 16-bit layers whose F*C_in
+// is a multiple of 4 only; 16-byte chunks and four chained 32x32x2 MFMAs for fp32
+// (whose K index inside the step is a permutation of the chunk order, the same one
+// for both operands, so the sum is unchanged).  Stores are 16 bytes in every case.
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
@@ -35,16 +37,16 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename TR>
+template <typename T>  // two results rounded to the 16-bit output type
 __device__ __forceinline__ unsigned pack2(float a, float b);
 template <>
-__device__ __forceinline__ unsigned pack2<F16Traits>(float a, float b) {
+__device__ __forceinline__ unsigned pack2<_Float16>(float a, float b) {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     h2 v = {(_Float16)a, (_Float16)b};
     return __builtin_bit_cast(unsigned, v);
 }
 template <>
-__device__ __forceinline__ unsigned pack2<BF16Traits>(float a, float b) {
+__device__ __forceinline__ unsigned pack2<__bf16>(float a, float b) {
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
     b2 v = {(__bf16)a, (__bf16)b};
     return __builtin_bit_cast(unsigned, v);
@@ -86,16 +88,21 @@ __device__ __forceinline__ unsigned small_div(unsigned t, unsigned mg, unsigned 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
 template <typename TR, int NT, int KHM, int KSM, int OCC, bool EXACT, bool RELU>
 __global__ void __launch_bounds__(256, OCC)
-conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
+conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ x, const typename TR::Vec *__restrict__ wp,
                    const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
     using T = typename TR::T;
     using Vec = typename TR::Vec;
     constexpr int EB = (int)sizeof(T);            // bytes per element
-    constexpr int E = 16 / EB;                    // elements per 16-byte chunk: 8 (16-bit types) or 4 (fp32);
-                                                  // a K-step is two chunks, one per half of the wave
+    constexpr int E = TR::kPerLane;               // elements per operand chunk (g.epc): a K-step is two chunks,
+                                                  // one per half of the wave
+    constexpr int ESH = E == 8 ? 3 : 2;           // log2(E)
+    constexpr int CB = E * EB;                    // bytes per operand chunk: 16, or 8 (16-bit types, E = 4)
+    using XV = std::conditional_t<CB == 16, u32x4, u32x2>;  // an input fragment as loaded
+    static_assert(sizeof(Vec) == CB && (CB == 16 || CB == 8), "operand chunks of 8 or 16 bytes");
+    constexpr int EO = 16 / EB;                   // elements per 16-byte chunk of the stored output
     constexpr int COLS = 32 * NT;                 // output columns per wave
     constexpr int PITCH = COLS * EB + 16;         // bytes per LDS row (padded)
-    constexpr int CHUNKS = COLS / E;              // 16-byte chunks per row
+    constexpr int CHUNKS = COLS / EO;             // 16-byte chunks per row
     constexpr int PASSES = (32 * CHUNKS + 63) / 64;
     constexpr int SLAB = 32 * PITCH;
     __shared__ __attribute__((aligned(16))) unsigned char lds_all[4 * SLAB];
@@ -119,7 +126,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     const int n_lo = ng * COLS;
     int e_lo, e_hi;
     fc_band_window(g, n_lo, n_lo + COLS, E, &e_lo, &e_hi);
-    const int q_per_kh = g.kwin / E;
+    const int q_per_kh = g.kwin >> ESH;
     const int e0 = e_lo + E * hf;  // this lane's extended channel at K-step 0
 
     // ---- filter fragments, resident for the kernel's lifetime -----------------
@@ -132,14 +139,16 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
             for (int nt = 0; nt < NT; ++nt) {
                 const int e = e0 + 2 * E * ks;
                 const int n = n_lo + 32 * nt + r;
-                u32x4 v = {0u, 0u, 0u, 0u};
+                Vec v;
+#pragma unroll
+                for (int i = 0; i < E; ++i) v[i] = (T)0.0f;
                 if (kh < KH && ks < KS && e < e_hi && n < g.NCo) {
-                    const int q = (e - g.e_min) >> (E == 8 ? 3 : 2);  // e >= e_min, both multiples of E
+                    const int q = (e - g.e_min) >> ESH;  // e >= e_min, both multiples of E
                     const long long ci = g.compact ? fc_compact_chunk<E>(g, kh, q, n)
                                                    : ((long long)kh * q_per_kh + q) * g.NCo + n;
                     if (ci >= 0) v = wp[ci];  // off-band chunks of the compact form are zeros
                 }
-                wf[kh][ks][nt] = __builtin_bit_cast(Vec, v);
+                wf[kh][ks][nt] = v;
             }
     // bias enters as a rank-1 MFMA: A = bias in K slot 0, B = 1 in K slot 0
     Vec bf[NT], ones;
@@ -198,7 +207,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
         const int idx = p * 64 + lane;
         st_row[p] = idx / CHUNKS;
         const int ch = idx - st_row[p] * CHUNKS;
-        st_col[p] = n_lo + E * ch;  // first output column of the chunk
+        st_col[p] = n_lo + EO * ch;  // first output column of the chunk
         const bool in = st_row[p] < 32 && st_col[p] < g.NCo;
         st_lds[p] = (in ? st_row[p] : 0) * PITCH + ch * 16;
         st_lin[p] = in ? (unsigned)EB * ((unsigned)st_row[p] * (unsigned)g.NCo + (unsigned)st_col[p]) : kOutOfRange;
@@ -208,8 +217,8 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     // Store pacing: the wave's next store burst is not issued before this time (ticks * 256).
     unsigned long long pace_next = a.pace ? (unsigned long long)wall_clock64() << 8 : 0ull;
 
-    u32x4 xf[KHM][KSM];
-    auto load_tile = [&](u32x4 (&dst)[KHM][KSM]) {
+    XV xf[KHM][KSM];
+    auto load_tile = [&](XV (&dst)[KHM][KSM]) {
         const unsigned t = wo0 + (unsigned)r;
         const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
         const unsigned wo = t - q * (unsigned)g.Wf_out;
@@ -236,7 +245,10 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 // (col and in_row are multiples of E)
                 const bool ok = rv && ((colok >> ks) & 1u);
                 const unsigned voff = ok ? (unsigned)EB * (unsigned)(pix0 + kh * g.in_row + 2 * E * ks) : kOutOfRange;
-                asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst[kh][ks]) : "v"(voff), "s"(xr) : "memory");
+                if constexpr (CB == 16)
+                    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst[kh][ks]) : "v"(voff), "s"(xr) : "memory");
+                else
+                    asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen" : "=v"(dst[kh][ks]) : "v"(voff), "s"(xr) : "memory");
             }
         }
     };
@@ -307,7 +319,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                 // four consecutive output columns of pixel r
                 unsigned char *dst = slab + r * PITCH + (32 * nt + 8 * q + 4 * hf) * EB;
                 if constexpr (EB == 2) {
-                    u32x2 pk = {pack2<TR>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2<TR>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
+                    u32x2 pk = {pack2<T>(acc[nt][4 * q], acc[nt][4 * q + 1]), pack2<T>(acc[nt][4 * q + 2], acc[nt][4 * q + 3])};
                     if (RELU) {
                         // max(v, 0) on the rounded 16-bit patterns as signed integers: negative
                         // values (sign bit set) become +0, everything else is unchanged
@@ -360,7 +372,7 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
                     const unsigned q = small_div(t, a.mgW, (unsigned)g.Wf_out);
                     const unsigned oc = (t - q * (unsigned)g.Wf_out) * (unsigned)g.NCo + (unsigned)st_col[p];
                     const bool ok = st_lin[p] != kOutOfRange && cur_m0 + (unsigned)st_row[p] < (unsigned)g.M &&
-                                    oc + (unsigned)E <= (unsigned)g.out_row;
+                                    oc + (unsigned)EO <= (unsigned)g.out_row;
                     off = ok ? (unsigned)EB * (q * (unsigned)g.out_row + oc) : kOutOfRange;
                 }
                 __builtin_amdgcn_raw_buffer_store_b128(v, yr, off, 0, 2 /* nt */);
@@ -407,7 +419,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                       \
     conv_stream_kernel<TR, NT, KHM, KSM, OCC, EX, RL><<<blocks, 256, 0, st>>>(              \
-        g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y)
+        g, a, (const T *)x, (const typename TR::Vec *)wp, (const T *)bias, (T *)y)
     if (exact && g.relu) FC_GO(true, true);
     else if (exact) FC_GO(true, false);
     else if (g.relu) FC_GO(false, true);
@@ -435,8 +447,11 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
     StreamShape sh;
     if (!fc_stream_shape(g, g.band, &sh)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    if (dt == FOLDCONV_F16) return launch_shape<F16Traits>(g, sh, x, w_pack, bias, y, st);
-    if (dt == FOLDCONV_BF16) return launch_shape<BF16Traits>(g, sh, x, w_pack, bias, y, st);
-    if (dt == FOLDCONV_F32) return launch_shape<F32ChunkTraits>(g, sh, x, w_pack, bias, y, st);
+    // the operand chunk the plan packed the filter in (g.epc) picks the traits
+    if (dt == FOLDCONV_F16 && g.epc == 8) return launch_shape<F16Traits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16 && g.epc == 8) return launch_shape<BF16Traits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_F16 && g.epc == 4) return launch_shape<F16HalfTraits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16 && g.epc == 4) return launch_shape<BF16HalfTraits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_F32 && g.epc == 4) return launch_shape<F32ChunkTraits>(g, sh, x, w_pack, bias, y, st);
     return (int)hipErrorInvalidValue;
 }

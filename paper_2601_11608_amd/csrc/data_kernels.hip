@@ -12,6 +12,7 @@ namespace {
 
 constexpr int kThreads = 256;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // a 16-byte lane access
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 inline unsigned blocks_for(long long work, int per_block, long long cap) {
     long long b = (work + per_block - 1) / per_block;
@@ -135,15 +136,18 @@ pad_filter_kernel(const U *__restrict__ w, U *__restrict__ wp, int taps, int C, 
 }
 
 // ---------------------------------------------------------------------------
-// Expanded filter -> MFMA operand order for 16-bit types:
-//   pack[kh][q][n][j] = w'[kh*kwin + 8*q + j][n],  j = 0..7  (16 bytes)
-// so that one lane's eight consecutive K values of one output column are a
-// single 16-byte load.
+// Expanded filter -> MFMA operand order, in chunks of E rows (ConvGeom.epc):
+//   pack[kh][q][n][j] = w'[kh*kwin + E*q + j][n],  j = 0..E-1  (16 bytes, or 8 for E = 4 of a 16-bit type)
+// so that one lane's E consecutive K values of one output column are a
+// single load.
 // ---------------------------------------------------------------------------
-template <typename U>  // uint16_t: chunks of 8 rows; uint32_t (fp32): chunks of 4
+template <int N> struct ChunkOf;
+template <> struct ChunkOf<16> { typedef u32x4 type; };
+template <> struct ChunkOf<8> { typedef u32x2 type; };
+
+template <typename U, int E>  // uint16_t: chunks of 8 or 4 rows; uint32_t (fp32): chunks of 4
 __global__ void __launch_bounds__(kThreads)
-pack_filter_kernel(const U *__restrict__ we, u32x4 *__restrict__ pack, int KH, int kwin, int NCo) {
-    constexpr int E = 16 / sizeof(U);
+pack_filter_kernel(const U *__restrict__ we, typename ChunkOf<E * sizeof(U)>::type *__restrict__ pack, int KH, int kwin, int NCo) {
     const int q_per_kh = kwin / E;
     const long long total = (long long)KH * q_per_kh * NCo;
     const long long stride = (long long)gridDim.x * kThreads;
@@ -154,23 +158,22 @@ pack_filter_kernel(const U *__restrict__ we, u32x4 *__restrict__ pack, int KH, i
         U v[E];
 #pragma unroll
         for (int j = 0; j < E; ++j) v[j] = srcp[(long long)j * NCo];
-        u32x4 out;
-        __builtin_memcpy(&out, v, 16);
+        typename ChunkOf<E * sizeof(U)>::type out;
+        __builtin_memcpy(&out, v, sizeof(out));
         pack[i] = out;
     }
 }
 
 // ---------------------------------------------------------------------------
 // Original filter -> compact MFMA operand storage (layout at fc_compact_chunk):
-// one thread per 16-byte chunk  cpk[ph][kh][j][co][0..7].  Only the non-zero
+// one thread per chunk  cpk[ph][kh][j][co][0..E-1].  Only the non-zero
 // blocks of the expanded filter exist in this form
 // (paper: "Potential Optimizations for Sparsity", storing just the non-zero blocks).
 // ---------------------------------------------------------------------------
-template <typename U>  // uint16_t: chunks of 8 rows; uint32_t (fp32): chunks of 4
+template <typename U, int E>  // as pack_filter_kernel
 __global__ void __launch_bounds__(kThreads)
-compact_filter_kernel(const U *__restrict__ w, u32x4 *__restrict__ cpk, int KH, int taps_c /* KW*C_in */,
-                      int Co, int cJ, int cgcd, long long total) {
-    constexpr int E = 16 / sizeof(U);
+compact_filter_kernel(const U *__restrict__ w, typename ChunkOf<E * sizeof(U)>::type *__restrict__ cpk, int KH,
+                      int taps_c /* KW*C_in */, int Co, int cJ, int cgcd, long long total) {
     const long long stride = (long long)gridDim.x * kThreads;
     for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
         const int co = (int)(i % Co);
@@ -185,8 +188,8 @@ compact_filter_kernel(const U *__restrict__ w, u32x4 *__restrict__ cpk, int KH, 
             const int t = E * j + e - ph * cgcd;  // row of the kh-th KW*C_in x C_out tap matrix
             v[e] = (t >= 0 && t < taps_c) ? w[((long long)kh * taps_c + t) * Co + co] : (U)0;
         }
-        u32x4 out;
-        __builtin_memcpy(&out, v, 16);
+        typename ChunkOf<E * sizeof(U)>::type out;
+        __builtin_memcpy(&out, v, sizeof(out));
         cpk[i] = out;
     }
 }
@@ -524,29 +527,37 @@ int fc_launch_crop_channels(const foldconv_plan_s *p, const void *y_pad, void *y
     return last_error();
 }
 
+// the operand chunks the packers write: 8 or 4 elements of a 16-bit type, 4 of fp32
+static bool chunk_ok(const ConvGeom &g) { return (g.eb == 2 && (g.epc == 8 || g.epc == 4)) || (g.eb == 4 && g.epc == 4); }
+
 int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream) {
-    if (elem_bytes * g.epc != 16 || g.kwin % g.epc != 0) return (int)hipErrorInvalidValue;
+    if (elem_bytes != g.eb || !chunk_ok(g) || g.kwin % g.epc != 0) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const long long total = (long long)g.KH * (g.kwin / g.epc) * g.NCo;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
-    if (elem_bytes == 2)
-        pack_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    if (elem_bytes == 2 && g.epc == 8)
+        pack_filter_kernel<uint16_t, 8><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    else if (elem_bytes == 2)
+        pack_filter_kernel<uint16_t, 4><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x2 *)w_pack, g.KH, g.kwin, g.NCo);
     else
-        pack_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+        pack_filter_kernel<uint32_t, 4><<<grid, kThreads, 0, st>>>((const uint32_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
     return last_error();
 }
 
 int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_compact, void *stream) {
-    if (elem_bytes * g.epc != 16 || g.FC % g.epc != 0) return (int)hipErrorInvalidValue;
+    if (elem_bytes != g.eb || !chunk_ok(g) || g.FC % g.epc != 0) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const long long total = (long long)fc_compact_phases(g) * g.KH * g.cJ * g.Co;
     const unsigned grid = blocks_for(total, kThreads, 1 << 16);
-    if (elem_bytes == 2)
-        compact_filter_kernel<uint16_t><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH,
-                                                                   g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
+    if (elem_bytes == 2 && g.epc == 8)
+        compact_filter_kernel<uint16_t, 8><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x4 *)w_compact, g.KH,
+                                                                      g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
+    else if (elem_bytes == 2)
+        compact_filter_kernel<uint16_t, 4><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x2 *)w_compact, g.KH,
+                                                                      g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
     else
-        compact_filter_kernel<uint32_t><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (u32x4 *)w_compact, g.KH,
-                                                                   g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
+        compact_filter_kernel<uint32_t, 4><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (u32x4 *)w_compact, g.KH,
+                                                                      g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
     return last_error();
 }
 

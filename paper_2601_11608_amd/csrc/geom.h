@@ -32,7 +32,10 @@ struct ConvGeom {
     int Co;      // bias period (C_out)
     int C;       // original input channels (band arithmetic)
     int F, KH, KW, pad_h, pad_w;
-    int epc;     // elements per 16-byte chunk: 8 for the 16-bit types, 4 for fp32
+    int epc;     // elements per operand chunk (what a lane loads of x' and of the filter per K-step half):
+                 // 8 for the 16-bit types (16 bytes), 4 for fp32 (16 bytes), and 4 for a 16-bit layer whose
+                 // F*C_in is a multiple of 4 but not of 8 (8-byte chunks, streaming kernel only)
+    int eb;      // bytes per element; stored output chunks are always 16 bytes = 16/eb elements
     int e_min, e_max;  // dense window of extended channels, [e_min, e_max)
     int kwin;          // e_max - e_min = KW'*FC = filter rows per kh
     int in_row;        // elements per input row  (Wf*FC)
@@ -67,8 +70,8 @@ FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int 
 // Compact storage of the expanded filter for the vector kernels.  Every output slot g
 // uses the same KW*C_in x C_out matrix per kh (the non-zero blocks of w' are copies of the original
 // taps; paper: "Potential Optimizations for Sparsity": keep only the non-zero blocks); slots differ
-// only in where that matrix starts, a = (g-p)*C_in - e_min rows into the window.  In 16-byte
-// chunks of E = epc rows (8 for the 16-bit types, 4 for fp32) the start falls on phase a mod E, a multiple of
+// only in where that matrix starts, a = (g-p)*C_in - e_min rows into the window.  In operand
+// chunks of E = epc rows (ConvGeom.epc) the start falls on phase a mod E, a multiple of
 // gcd(C_in, E), so one zero-padded copy per phase serves every slot:
 //   cpk[ph][kh][j][co][i] = w[kh][t / C_in][t % C_in][co],  t = E*j + i - ph*gcd,  0 <= t < KW*C_in, else 0.
 // Returns the chunk of cpk that equals rows [e_min+E*q, e_min+E*q+E) of column n of w', or -1 when
@@ -76,7 +79,7 @@ FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int 
 // E is a template argument (it must equal g.epc) so that the kernels divide by shifting.
 template <int E>
 FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
-    static_assert(E == 4 || E == 8, "16-byte chunks of a 32-bit or a 16-bit type");
+    static_assert(E == 4 || E == 8, "chunks of 4 or 8 elements");
     constexpr int SH = E == 8 ? 3 : 2;
     const int slot = n / g.Co, co = n - slot * g.Co;
     const int a = (slot - g.pad_w) * g.C - g.e_min;  // >= 0 because e_min <= -p*C_in

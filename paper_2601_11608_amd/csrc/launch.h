@@ -7,13 +7,13 @@
 // --- kernel choice and its tiling facts (select.cpp) -------------------------
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt);
 int fc_band_tile_n(int kernel, const ConvGeom &g);  // output columns sharing one band window (for g's walk, g.band)
-int fc_band_align(int kernel, foldconv_dtype_t dt); // alignment of the band window in elements
+int fc_band_align(int kernel, const ConvGeom &g);   // alignment of the band window in elements
 
 // Shape of the streaming kernel instance for a geometry; false if none fits.
 struct StreamShape {
     int inst;    // index into FC_STREAM_INSTANCES
     int nt;      // 32-column MFMA tiles held per wave
-    int ksteps;  // 16-wide K-steps per kh actually walked
+    int ksteps;  // K-steps (two operand chunks each) per kh actually walked
 };
 // Compiled instances of the streaming kernel: X(NT, max KH, max K-steps per kh, workgroups per CU).
 // Filter fragments cost 4*NT*KH*ksteps registers per lane, which bounds the list.

@@ -46,18 +46,19 @@ static double issued_flops(ConvGeom g, int band, int tile_n, int kstep, int alig
 static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t dtype) {
     g.band = band;
     const bool f32 = dtype == FOLDCONV_F32;
-    const int align = fc_band_align(plan_kernel, dtype);
+    const int align = fc_band_align(plan_kernel, g);
     if (plan_kernel == FC_KERNEL_GATHER) return issued_flops(g, band, 32, f32 ? 2 : 16, 1, false, 0);
-    // the vector kernels walk K in steps of two 16-byte chunks: 16 elements of a 16-bit type, 8 of fp32
-    // (there as four MFMAs of K = 2)
-    const int kstep = f32 ? 8 : 16;
+    // the vector kernels walk K in steps of two operand chunks: 16 elements of a 16-bit type (8 where the
+    // chunks are 8 bytes), 8 of fp32 (there as four MFMAs of K = 2)
+    const int kstep = 2 * g.epc;
     if (plan_kernel == FC_KERNEL_STREAM) {
         StreamShape sh;
         if (!band && fc_stream_lds_ok(g)) return issued_flops(g, 0, 64, kstep, align, false, 0);  // bias added in fp32
-        // the rank-1 bias product: one 16-wide MFMA, or one of K = 2 for fp32
-        if (fc_stream_shape(g, band, &sh)) return issued_flops(g, band, 32 * sh.nt, kstep, align, false, f32 ? 2 : 16);
-        // fp32 has no tiled kernel: a dense walk too long for the streaming instances runs the gather kernel
-        if (f32) return issued_flops(g, band, 32, 2, 1, false, 0);
+        // the rank-1 bias product: one MFMA of the K-step's width, or one of K = 2 for fp32
+        if (fc_stream_shape(g, band, &sh)) return issued_flops(g, band, 32 * sh.nt, kstep, align, false, f32 ? 2 : kstep);
+        // where the tiled kernel does not serve the layer, a dense walk too long for the streaming instances
+        // runs the gather kernel
+        if (!fc_tiled_ok(g)) return issued_flops(g, band, 32, f32 ? 2 : 16, 1, false, 0);
     }
     return issued_flops(g, band, fc_tiled_bn(g), kstep, align, true, 16);
 }
@@ -69,7 +70,7 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 // with the rates these kernels sustain on MI355X (fitted to the timings of every legal power-of-two
 // fold factor of the benchmark layers, rotating buffers, graph replay):
 //   * memory: x + y + filter bytes at 6.2 TB/s (of the 8 TB/s HBM peak), 7.0 TB/s for launches of the streaming
-//     kernel long enough to pace their store stream (64 MB and more).  On the streaming kernel a wave
+//     kernel long enough to pace their store stream (64 MB and more); 5 % less with 8-byte operand chunks.  On the streaming kernel a wave
 //     owns 64 (or 128) output columns, so y counts at F*C_out rounded up to whole waves: idle
 //     lanes store nothing but take their turn (tile alignment);
 //   * matrix: issued MFMA flops (band walk, tile padding and the rank-1 bias product included) at
@@ -79,14 +80,17 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 //   * filter term: the expanded filter read at 1 TB/s (every wave fetches its own fragments; a larger
 //     F buys nothing once F*C_in is aligned, and its F^2 larger filter is not free);
 //   * overhead: 4.5 us (streaming), 8 us (tiled), 10 us (gather) per launch.
-static double model_seconds(const foldconv_shapes_t &s, int wave_columns) {
+static double model_seconds(const foldconv_shapes_t &s, int wave_columns, bool half_chunks) {
     const double x = (double)s.x_bytes, y = (double)s.y_bytes;
     const double wf = s.prefer_compact ? (double)s.filter_compact_bytes : (double)s.w_exp_bytes;
-    const double hbm = (s.conv_kernel == FC_KERNEL_STREAM && x + y >= 64e6) ? 7.0e12 : 6.2e12;
+    double hbm = (s.conv_kernel == FC_KERNEL_STREAM && x + y >= 64e6) ? 7.0e12 : 6.2e12;
+    if (half_chunks) hbm *= 0.95;  // twice the load instructions and MFMAs per K value: 69 against 66 us on the 411 MB layer
     double overhead, rate, y_eff = y;
     if (s.conv_kernel == FC_KERNEL_STREAM) {
         overhead = 4.5e-6;
-        rate = s.dtype == FOLDCONV_F32 ? 0.08e15 : 1.0e15;  // fp32: K = 2 MFMAs, 157 TFLOP/s peak
+        // fp32: K = 2 MFMAs, 157 TFLOP/s peak; 8-byte operand chunks: K = 8 MFMAs at half the rate of K = 16
+        // (0.19 PFLOP/s measured on the guarded nine-step instance, 0.35 and more on the exact two-step one)
+        rate = s.dtype == FOLDCONV_F32 ? 0.08e15 : half_chunks ? 0.33e15 : 1.0e15;
         const double cols = (double)((s.Co_fold + wave_columns - 1) / wave_columns) * wave_columns;
         y_eff = y * cols / (double)s.Co_fold;
     } else if (s.conv_kernel == FC_KERNEL_TILED) {
@@ -171,7 +175,9 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     g.pad_h = pad_h; g.pad_w = pad_w;
     g.e_min = (int)(d_min * FC); g.e_max = (int)((d_max + 1) * FC); g.kwin = g.e_max - g.e_min;
     g.in_row = (int)(Wf * FC); g.out_row = (int)(W_out * C_out); g.M = M;
-    g.epc = 16 / eb;
+    g.eb = eb;
+    // operand chunks of 16 bytes; 8-byte chunks for a 16-bit layer whose folded channel count allows no more
+    g.epc = (eb == 2 && FC % 8 != 0 && FC % 4 == 0) ? 4 : 16 / eb;
     g.cgcd = fc_gcd_chunk(C_in, g.epc);
     g.cJ = (g.epc - g.cgcd + KW * C_in + g.epc - 1) / g.epc;
 
@@ -182,7 +188,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     q.pad_h = pad_h; q.pad_w = pad_w;
     q.e_min = -pad_w * C_pad; q.e_max = (KW - pad_w) * C_pad; q.kwin = q.e_max - q.e_min;
     q.in_row = W * C_pad; q.out_row = (int)(W_out * Co_pad); q.M = M_pad;
-    q.epc = 16 / eb;
+    q.eb = eb; q.epc = 16 / eb;
     q.cgcd = q.epc; q.cJ = KW * C_pad / q.epc;
 
     s.conv_kernel = fc_choose_kernel(g, dtype);
@@ -210,7 +216,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     // phase for the vector kernels; the gather kernel reads the original filter as it is.
     s.filter_compact_bytes = (long long)align_up(
         s.conv_kernel == FC_KERNEL_GATHER ? (size_t)s.w_bytes
-                                          : (size_t)fc_compact_phases(g) * KH * g.cJ * C_out * 16, 256);
+                                          : (size_t)fc_compact_phases(g) * KH * g.cJ * C_out * (g.epc * eb), 256);
     p->ws_xpad = 0;
     p->ws_wpad = align_up((size_t)xpad_bytes, 256);
     p->ws_wpack = p->ws_wpad + align_up((size_t)wpad_bytes, 256);
@@ -226,7 +232,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     s.issued_flops_dense = walk_flops(s.conv_kernel, g, 0, dtype);
     s.issued_flops_band = walk_flops(s.conv_kernel, g, 1, dtype);
     s.issued_flops_padded = walk_flops(s.padded_kernel, q, 1, dtype);
-    s.model_seconds = model_seconds(s, fc_band_tile_n(s.conv_kernel, g));
+    s.model_seconds = model_seconds(s, fc_band_tile_n(s.conv_kernel, g), g.epc * eb == 8);
 
     *out = p;
     return FOLDCONV_OK;

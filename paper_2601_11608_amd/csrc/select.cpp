@@ -24,22 +24,24 @@ int max_ksteps(ConvGeom g, int band, int cols) {
 
 // Conditions shared by the vector kernels.
 static bool vector_ok(const ConvGeom &g) {
-    // 16-byte chunks everywhere: folded channels, output columns and stored rows in multiples of a chunk
-    // (8 elements of a 16-bit type, 4 of fp32).
-    const int E = g.epc;
-    if (E != 8 && E != 4) return false;
-    if (g.FC % E != 0 || g.NCo % E != 0 || g.out_row % E != 0 || g.kwin % E != 0) return false;
+    // Operand side: folded channels and the filter window in multiples of the operand chunk (8 elements of a
+    // 16-bit type, or 4 where F*C_in allows no more; 4 of fp32).  Output side: columns and stored rows in
+    // multiples of a 16-byte chunk.
+    const int E = g.epc, EO = 16 / g.eb;
+    if (!((g.eb == 2 && (E == 8 || E == 4)) || (g.eb == 4 && E == 4))) return false;
+    if (g.FC % E != 0 || g.kwin % E != 0 || g.NCo % EO != 0 || g.out_row % EO != 0) return false;
     // 32-bit byte offsets into x and into the packed filter, 32-bit chunk index into y.
-    const long long eb = 16 / E;
+    const long long eb = g.eb;
     const long long x_elems = (long long)g.N * g.H * g.in_row;
     const long long y_elems = (long long)g.N * g.Hout * g.out_row;
     const long long w_elems = (long long)g.KH * g.kwin * g.NCo;
-    if ((x_elems + 4LL * g.in_row) * eb >= (1LL << 31) || y_elems / E >= (1LL << 32) || w_elems * eb >= (1LL << 31)) return false;
+    if ((x_elems + 4LL * g.in_row) * eb >= (1LL << 31) || y_elems / EO >= (1LL << 32) || w_elems * eb >= (1LL << 31)) return false;
     return true;
 }
 
-// the LDS-tiled kernel and the two variants of the streaming kernel below exist for the 16-bit types only
-bool fc_tiled_ok(const ConvGeom &g) { return g.epc == 8 && vector_ok(g); }
+// the LDS-tiled kernel and the two variants of the streaming kernel below exist for the 16-bit types in
+// 16-byte operand chunks only
+bool fc_tiled_ok(const ConvGeom &g) { return g.eb == 2 && g.epc == 8 && vector_ok(g); }
 
 int fc_tiled_bn(const ConvGeom &g) {
     // Multiplies issued by a tile width = sum over its N tiles of (K blocks inside the tile's band
@@ -68,18 +70,19 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
     // exact multiply-high division of (tile start + lane) by the folded width and by the output height
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     // 32-bit byte offsets from a tile's first output row to its last (up to 33 rows further on)
-    if (34LL * g.out_row * (16 / g.epc) >= (1LL << 31) || 34LL * g.NCo * (16 / g.epc) >= (1LL << 31)) return false;
+    if (34LL * g.out_row * g.eb >= (1LL << 31) || 34LL * g.NCo * g.eb >= (1LL << 31)) return false;
     // 64 columns per wave first: for the small-C_in layers this is one K-step per kh with the
     // fewest structural-zero products; wider waves only when no such instance fits.
     static const int prefer[] = {2, 4};
     for (int nt : prefer) {
-        if (g.epc == 4 && nt > 2) continue;  // fp32: 64 columns per wave only (LDS for the waves' output slabs)
+        if (g.eb == 4 && nt > 2) continue;  // fp32: 64 columns per wave only (LDS for the waves' output slabs)
         const int ks = max_ksteps(g, band, 32 * nt);
         // Beyond a dozen K-steps per tile the layer is bound by the matrix cores, not by the
         // output stream, and the LDS-tiled kernel (operands shared by four waves) is the better
         // tool.  The dense walk of a small-K layer may still use the largest instance.
-        // (fp32 has no tiled kernel: any instance that fits is better than the element-gather kernel.)
-        if (band && g.epc == 8 && g.KH * ks > 12) continue;
+        // (Where the tiled kernel does not serve the layer (fp32, 8-byte operand chunks) any instance that
+        // fits is better than the element-gather kernel.)
+        if (band && fc_tiled_ok(g) && g.KH * ks > 12) continue;
         for (int i = 0; i < kNumInst; ++i)
             if (kInst[i].nt == nt && g.KH <= kInst[i].khm && ks <= kInst[i].ksm) {
                 out->inst = i;
@@ -92,7 +95,7 @@ bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out) {
 }
 
 bool fc_stream_lds_ok(const ConvGeom &g) {
-    if (g.epc != 8 || !vector_ok(g)) return false;
+    if (g.eb != 2 || g.epc != 8 || !vector_ok(g)) return false;
     if (g.Wf_out >= 65000 || g.Hout >= 65000) return false;
     if (34LL * g.out_row * 2 >= (1LL << 31) || 34LL * g.NCo * 2 >= (1LL << 31)) return false;
     if (g.M >= (1LL << 31) - (1LL << 20)) return false;
@@ -108,7 +111,7 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
     // g.out_row is the plan's unfolded W_out here: elements per channel row of y for a width fold, rows per
     // channel plane for a height fold (the plan is the transposed image's).
     // one wave per 64 columns, at most 16 waves, 4 channels per LDS read
-    if (g.epc != 8 || g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
+    if (g.eb != 2 || g.epc != 8 || g.FC % 8 != 0 || g.kwin % 8 != 0 || g.Co % 4 != 0) return false;
     if (g.NCo % 64 != 0 || g.NCo > 1024) return false;
     if (height_fold) {
         // 16-byte pieces run along the image width = the plan's rows: whole pieces of 8 columns; a thread of the
@@ -133,10 +136,10 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
 }
 
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt) {
-    // Channel counts that miss the 16-byte chunk alignment, and fp32 layers too large for the
+    // Channel counts that miss the chunk alignment, and fp32 or 8-byte-chunk layers too large for the
     // streaming kernel's registers, run the element-gather MFMA kernel (the analogue of
     // Algorithm 1's fallback: it is correct for every shape, just not fast).
-    (void)dt;  // the element size is in g.epc
+    (void)dt;  // element size and operand chunk are in g
     StreamShape sh;
     if (fc_stream_shape(g, 1, &sh)) return FC_KERNEL_STREAM;
     if (fc_tiled_ok(g)) return FC_KERNEL_TILED;
@@ -152,7 +155,7 @@ int fc_band_tile_n(int kernel, const ConvGeom &g) {
     }
 }
 
-int fc_band_align(int kernel, foldconv_dtype_t dt) {
+int fc_band_align(int kernel, const ConvGeom &g) {
     if (kernel == FC_KERNEL_GATHER) return 1;
-    return dt == FOLDCONV_F32 ? 4 : 8;
+    return g.epc;
 }

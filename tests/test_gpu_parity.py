@@ -241,10 +241,13 @@ def test_dense_walk_with_staged_input(fc, oracle, case, dt):
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
 @pytest.mark.parametrize("KH,KW,C,Co,F,pad", [(3, 3, 3, 64, 16, 1), (1, 9, 1, 64, 32, 4), (5, 1, 1, 1, 8, 0),
                                                (3, 3, 12, 48, 4, 1), (2, 4, 2, 8, 4, 2), (3, 3, 132, 256, 4, 1),
-                                               (3, 3, 20, 36, 4, 1), (1, 1, 5, 7, 8, 0), (3, 5, 6, 10, 4, 2)])
+                                               (3, 3, 20, 36, 4, 1), (1, 1, 5, 7, 8, 0), (3, 5, 6, 10, 4, 2),
+                                               # F*C_in = 12, 12, 4: chunks of 4 rows (8 bytes)
+                                               (3, 3, 3, 64, 4, 1), (3, 3, 6, 24, 2, 1), (1, 7, 2, 40, 2, 3)])
 def test_compact_filter_holds_the_band_of_the_expanded_filter(fc, oracle, KH, KW, C, Co, F, pad, dt):
-    """Every 8-row chunk of every column of the oracle's expanded filter is either all zero or
-    found, bit for bit, where the compact layout says it is; the compact form is much smaller."""
+    """Every chunk (8 rows, or 4 where F*C_in is a multiple of 4 only) of every column of the oracle's
+    expanded filter is either all zero or found, bit for bit, where the compact layout says it is;
+    the compact form is much smaller."""
     w = draw((KH, KW, C, Co), dt, 12)
     plan = fc.foldconv_plan(1, 8, 8 * F, C, Co, KH, KW, pad, F, w.dtype)
     s = plan.shapes
@@ -252,10 +255,11 @@ def test_compact_filter_holds_the_band_of_the_expanded_filter(fc, oracle, KH, KW
     ws = torch.full((int(s.filter_compact_bytes),), 0xFF, dtype=torch.uint8, device="cuda")
     fc.foldconv_pack_filter_compact(plan, w.cuda(), ws)
     torch.cuda.synchronize()
-    g8 = int(np.gcd(C, 8))
-    P, cJ = 8 // g8, (8 - g8 + KW * C + 7) // 8
-    assert s.filter_compact_bytes == -(-P * KH * cJ * Co * 16 // 256) * 256
-    cpk = ws.cpu().numpy().view(np.int16)[: P * KH * cJ * Co * 8].reshape(P, KH, cJ, Co, 8)
+    E = 8 if (F * C) % 8 == 0 else 4
+    g8 = int(np.gcd(C, E))
+    P, cJ = E // g8, (E - g8 + KW * C + E - 1) // E
+    assert s.filter_compact_bytes == -(-P * KH * cJ * Co * 2 * E // 256) * 256
+    cpk = ws.cpu().numpy().view(np.int16)[: P * KH * cJ * Co * E].reshape(P, KH, cJ, Co, E)
     w_exp = oracle.expand_filter(bits_as_f64(w), F, s.pad_w).astype(np.int16)        # [KH, KW', FC, FCo] bit patterns
     w_exp = w_exp.reshape(KH, s.KW_fold * F * C, F * Co)
     e_min = s.d_min * F * C
@@ -263,12 +267,12 @@ def test_compact_filter_holds_the_band_of_the_expanded_filter(fc, oracle, KH, KW
     for g in range(F):
         a = (g - s.pad_w) * C - e_min
         assert a >= 0
-        for q in range(w_exp.shape[1] // 8):
-            rows = w_exp[:, 8 * q:8 * q + 8, g * Co:(g + 1) * Co]                      # [KH, 8, Co]
-            j = q - (a >> 3)
+        for q in range(w_exp.shape[1] // E):
+            rows = w_exp[:, E * q:E * q + E, g * Co:(g + 1) * Co]                      # [KH, E, Co]
+            j = q - a // E
             if 0 <= j < cJ:
-                assert np.array_equal(cpk[(a & 7) // g8, :, j].transpose(0, 2, 1), rows), (g, q)
-                used[(a & 7) // g8, :, j] = True
+                assert np.array_equal(cpk[(a % E) // g8, :, j].transpose(0, 2, 1), rows), (g, q)
+                used[(a % E) // g8, :, j] = True
             else:
                 assert not rows.any(), (g, q)
     if F >= P:                                   # every phase copy serves some slot: what no slot reads is padding
@@ -434,6 +438,45 @@ def test_fp32_layers_on_the_streaming_kernel(fc, oracle, case):
         assert_elementwise(f64(y), ref, S, K, dt, "%s %s" % (case, name))
     # the compact filter feeds the same values to the same MFMA slots as the packed one
     assert np.array_equal(bits(run_compact(fc, plan, x, w, b, rflag)), bits(y_band))
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("case", [(4, 60, 300, 3, 64, 3, 3, 1, 4, True, False),      # W = 300 = 4 * 75: no fold reaches 8 channels
+                                  (3, 28, 28, 1, 32, 3, 3, 1, 4, True, True),        # one input channel, W = 28 = 4 * 7
+                                  (2, 33, 36, 6, 24, 3, 3, 1, 2, False, False),      # F*C_in = 12, several K-steps per kh
+                                  (2, 20, 24, 20, 16, 3, 3, 1, 1, True, False),      # unfolded, C_in = 20: eight K-steps per kh
+                                  (1, 1, 6000, 2, 40, 1, 7, 3, 2, False, True)],     # 1-D
+                         ids=lambda c: "x".join(map(str, c[:9])))
+def test_sixteen_bit_layers_in_eight_byte_chunks(fc, oracle, case, dt):
+    """16-bit tensors whose folded channel count is a multiple of 4 but not of 8 run the streaming
+    kernel with 8-byte operand chunks (K-steps of 8 on the 32x32x8 MFMA) instead of the element-gather
+    kernel.  Every walk and the zero-padded reference against the oracle, rel-L2 and element by
+    element (paper: Eq. new_conv_H; the alignment remark on F in the IR formulation)."""
+    N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
+    assert (F * C) % 8 == 4
+    x = draw((N, H, W, C), dt, 81)
+    w = (draw((KH, KW, C, Co), dt, 82) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+    b = draw((Co,), dt, 83) if hb else None
+    ph, pw = oracle.axis_pads(KH, KW, pad)
+    ref = oracle.conv_direct(f64(x), f64(w), None if b is None else f64(b), ph, pw, relu)
+    plan = fc.foldconv_plan(N, H, W, C, Co, KH, KW, pad, F, x.dtype)
+    assert plan.shapes.conv_kernel == 2 and plan.shapes.workspace_bytes >= plan.shapes.w_exp_bytes
+    rflag = fc.FLAG_RELU if relu else 0
+    S, K = abs_sum(oracle, x, w, b, ph, pw), KH * KW * C
+    y_band = run_folded(fc, plan, x, w, b, rflag)
+    y_compact = run_compact(fc, plan, x, w, b, rflag)
+    for name, y in (("band", y_band),
+                    ("dense", run_folded(fc, plan, x, w, b, rflag | fc.FLAG_DENSE_K)),
+                    ("compact", y_compact),
+                    ("compact dense", run_compact(fc, plan, x, w, b, rflag | fc.FLAG_DENSE_K)),
+                    ("padded", run_padded(fc, plan, x, w, b, rflag))):
+        assert not bool(torch.isnan(y).any()), (case, name)
+        err = rel_l2_per_image(f64(y), ref)
+        print("%s %s %s: rel-L2 %.2e" % (dt, case[:9], name, err), flush=True)
+        assert err <= TOL[dt], (case, name, err)
+        assert_elementwise(f64(y), ref, S, K, dt, "%s %s" % (case, name))
+    # the compact filter feeds the same values to the same MFMA slots as the packed one
+    assert np.array_equal(bits(y_compact), bits(y_band))
 
 
 @pytest.mark.parametrize("dt", ["f16", "bf16", "f32"])

@@ -241,6 +241,12 @@ def test_compact_filter_size(fc):
     # fp32 on the streaming kernel: chunks of 4 rows, 4/gcd(C_in,4) copies
     s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 8, "float32").shapes
     assert s.conv_kernel == 2 and s.filter_compact_bytes == (4 * 3 * ((4 - 1 + 9 + 3) // 4) * 16 * 16 + 255) // 256 * 256
+    # a 16-bit layer whose F*C_in is a multiple of 4 only: streaming kernel, 8-byte chunks of 4 rows
+    s = fc.foldconv_plan(4, 60, 300, 3, 64, 3, 3, 1, 4, "float16").shapes
+    assert s.conv_kernel == 2 and s.filter_compact_bytes == (4 * 3 * ((4 - 1 + 9 + 3) // 4) * 64 * 8 + 255) // 256 * 256
+    assert s.workspace_bytes >= s.w_exp_bytes
+    # ... but only where the output side still has whole 16-byte chunks (F*C_out a multiple of 8)
+    assert fc.foldconv_plan(4, 60, 300, 3, 5, 3, 3, 1, 4, "float16").shapes.conv_kernel == 0
     # the gather kernel (channels off the chunk alignment) reads the original filter itself
     s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 1, "float32").shapes
     assert s.conv_kernel == 0 and s.filter_compact_bytes == (s.w_bytes + 255) // 256 * 256

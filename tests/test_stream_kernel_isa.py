@@ -63,7 +63,7 @@ def test_hand_counted_waits_cover_every_fragment(asm):
         # 16-byte store passes per 32-row tile of 32*nt columns: 8 elements per piece, 4 for fp32
         passes = (4 if "F32ChunkTraits" in name else 2) * nt
         lines = loop_lines(asm, name)
-        loads = [i for i, l in enumerate(lines) if l.startswith("buffer_load_dwordx4")]
+        loads = [i for i, l in enumerate(lines) if re.match(r"buffer_load_dwordx[24] ", l)]   # dwordx2: 8-byte operand chunks
         assert len(loads) == khm * ksm, name
         stores_after = sum(1 for l in lines[loads[-1]:] if l.startswith("buffer_store_dwordx4"))
         waits = [int(w) for l in lines for w in re.findall(r"s_waitcnt vmcnt\((\d+)\)", l)]
@@ -75,7 +75,7 @@ def test_hand_counted_waits_cover_every_fragment(asm):
         assert stores_after >= passes - 1, name
         need = {}
         for pos, i in enumerate(loads):
-            mm = re.match(r"buffer_load_dwordx4 v\[(\d+):(\d+)\]", lines[i])
+            mm = re.match(r"buffer_load_dwordx[24] v\[(\d+):(\d+)\]", lines[i])
             for r in range(int(mm.group(1)), int(mm.group(2)) + 1):
                 need[r] = (len(loads) - 1 - pos) + passes
         waited = 10 ** 9
@@ -88,7 +88,7 @@ def test_hand_counted_waits_cover_every_fragment(asm):
                 assert r not in need or waited <= need[r], "%s: '%s' touches v%d before its load landed" % (name, l, r)
         pending = set()
         for l in lines[loads[0]:]:
-            mm = re.match(r"buffer_load_dwordx4 v\[(\d+):(\d+)\]", l)
+            mm = re.match(r"buffer_load_dwordx[24] v\[(\d+):(\d+)\]", l)
             if mm:
                 pending.update(range(int(mm.group(1)), int(mm.group(2)) + 1))
                 continue
@@ -168,7 +168,7 @@ def walk_paths(lines, name):
                 pc += 1
                 continue
             touched = vregs(l)
-            m = re.match(r"buffer_load_dwordx4 v\[(\d+):(\d+)\]", l)
+            m = re.match(r"buffer_load_dwordx[24] v\[(\d+):(\d+)\]", l)
             for regs, _ in state:
                 assert not (touched & regs), "%s: '%s' touches registers of a load in flight" % (name, l)
             if re.match(r"(buffer|global|flat|scratch)_(load|store|atomic)", l):
