@@ -82,7 +82,7 @@ enum {
                                          memory), for width- and height-folded plans.  Only where
                                          shapes.out_nchw_fused is 1, else
                                          FOLDCONV_ERR_UNSUPPORTED; excludes KEEP_FOLDED          */
-    FOLDCONV_FLAG_UNPACED = 64u       /* do not pace the store stream.  Long write-bound launches
+    FOLDCONV_FLAG_UNPACED = 64u,      /* do not pace the store stream.  Long write-bound launches
                                          of the streaming kernels hold each wave's store burst to a
                                          schedule on the GPU's wall clock, set for a launch that
                                          has the whole memory system to itself (about 10 % faster
@@ -90,6 +90,16 @@ enum {
                                          other work beside the launch, or wants to measure the
                                          difference, passes this flag.  Same result either way.
                                          Also accepted by conv_padded_forward                    */
+    FOLDCONV_FLAG_IN_NCHW = 128u      /* x_fold is the channels-first image itself,
+                                         [N][C_in][H][W] (what foldconv_fold_input_nchw would
+                                         read): the launch applies the fold in its load
+                                         addressing and no folded copy is made.  Only together
+                                         with FOLDCONV_FLAG_OUT_NCHW (FOLDCONV_ERR_BADARG
+                                         without) and for height-folded plans whose
+                                         shapes.out_nchw_fused is 1 (else
+                                         FOLDCONV_ERR_UNSUPPORTED: with a width fold the lanes of
+                                         such a read lie F elements apart, and the separate fold
+                                         pass is faster); same bits as the two-step route         */
 };
 
 /* Which image axis of a channels-first (NCHW) tensor is folded into the channels. */
@@ -292,7 +302,10 @@ FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *
  * compact filter (shapes.filter_compact_bytes) and w_exp is ignored.
  * With FOLDCONV_FLAG_OUT_NCHW the reconstructed output is written
  * channels-first, y[n][co][h][F*w'+g] for a width fold and
- * y[n][co][F*h'+g][w] for a height fold (shapes.y_bytes, 16-byte aligned).
+ * y[n][co][F*h'+g][w] for a height fold (shapes.y_bytes, 16-byte aligned);
+ * with FOLDCONV_FLAG_IN_NCHW as well (height folds), x_fold is the
+ * channels-first input x[n][c][h][w] (paper: Eq. "width_fold_def" along h,
+ * x'[n][w][h'][f*C+c] = x[n][c][F*h'+f][w], applied on the fly).
  */
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,

@@ -18,6 +18,7 @@ FLAG_FILTER_PACKED = 8
 FLAG_FILTER_COMPACT = 16
 FLAG_OUT_NCHW = 32
 FLAG_UNPACED = 64
+FLAG_IN_NCHW = 128
 FOLD_W = 0
 FOLD_H = 1
 STATIC_SCRATCH_BYTES = 16 << 20

@@ -11,7 +11,7 @@ static int hip_status(int e) { return e == 0 ? FOLDCONV_OK : FOLDCONV_ERR_HIP; }
 
 static const unsigned kAllFlags =
     FOLDCONV_FLAG_RELU | FOLDCONV_FLAG_DENSE_K | FOLDCONV_FLAG_KEEP_FOLDED | FOLDCONV_FLAG_FILTER_PACKED |
-    FOLDCONV_FLAG_FILTER_COMPACT | FOLDCONV_FLAG_OUT_NCHW | FOLDCONV_FLAG_UNPACED;
+    FOLDCONV_FLAG_FILTER_COMPACT | FOLDCONV_FLAG_OUT_NCHW | FOLDCONV_FLAG_UNPACED | FOLDCONV_FLAG_IN_NCHW;
 
 extern "C" int foldconv_expand_filter(foldconv_plan_t plan, const void *w, void *w_exp, void *stream) {
     if (!plan_ok(plan) || !w || !w_exp || w == w_exp) return FOLDCONV_ERR_BADARG;
@@ -118,6 +118,9 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
 
     int kernel = s.conv_kernel;
     const bool out_nchw = (flags & FOLDCONV_FLAG_OUT_NCHW) != 0;
+    const bool in_nchw = (flags & FOLDCONV_FLAG_IN_NCHW) != 0;
+    if (in_nchw && !out_nchw) return FOLDCONV_ERR_BADARG;  // only the channels-first kernel gathers its input
+    if (in_nchw && plan->fold_axis != FOLDCONV_FOLD_H) return FOLDCONV_ERR_UNSUPPORTED;  // ... and only along h
     const bool hfold = plan->fold_axis == FOLDCONV_FOLD_H;
     if (out_nchw) {
         if (flags & FOLDCONV_FLAG_KEEP_FOLDED) return FOLDCONV_ERR_BADARG;
@@ -141,7 +144,7 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
             if (!fc_stream_shape(g, g.band, &sh)) g.band = 1;
         }
         if (out_nchw)
-            return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, x_fold, workspace, bias, y, stream));
+            return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, in_nchw, x_fold, workspace, bias, y, stream));
         return hip_status(
             fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, workspace, workspace, bias, y, stream));
     }
@@ -160,7 +163,7 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
         }
     }
     if (out_nchw)
-        return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, x_fold, workspace, bias, y, stream));
+        return hip_status(fc_launch_conv_stream_nchw((foldconv_dtype_t)s.dtype, g, hfold, in_nchw, x_fold, workspace, bias, y, stream));
     return hip_status(fc_launch_conv(kernel, (foldconv_dtype_t)s.dtype, g, x_fold, w_exp, workspace, bias, y, stream));
 }
 

@@ -25,6 +25,15 @@
 // before either is written out, so that eight neighbouring lanes store 64 consecutive image
 // columns of a channel row: whole 128-byte lines (half lines, written tile by tile, cost a
 // quarter of the launch).
+//
+// XN instances (height folds) read a channels-first input as well: the folded pixel's channel f*C_in + c of
+// plan row a is x[n][c][F*b'+f][a], so a lane's fragment of eight K-contiguous values is gathered with eight
+// 2-byte loads (one register each, paired up after they land: on this GPU a 16-bit load into one half of a
+// register clears the other half).  The 32 pixels of a tile are consecutive plan rows a, so the lanes of a
+// load read 64 consecutive bytes of one image row; the separate fold pass and its round trip through memory
+// fall away (paper: Eq. "width_fold_def", along h, applied in the load addressing).  For a width fold the
+// same gather would have the lanes F elements apart (x[n][c][a][F*b'+f], b' across the lanes): measured
+// three times slower than the fold pass it replaces, so those plans keep the pass.
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
 // w = F w' + f (h = F h' + f for a height fold), applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
@@ -67,6 +76,9 @@ struct NchwArgs {
     int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
     unsigned tiles_ab;    // HF: tile pairs per folded column, ceil(Hout / 64)
     unsigned pace;        // wall-clock ticks * 256 between a workgroup's store bursts, 0 = unpaced (fc_store_pace)
+    // XN: element strides of the channels-first input: one channel plane, one step along the plan's rows,
+    // one step along the plan's (unfolded) columns
+    unsigned xP, xsA, xsB;
 };
 
 template <int I, int N, class F>
@@ -83,7 +95,7 @@ __device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigne
 }
 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
-template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF>
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN>
 __global__ void __launch_bounds__(1024, 1)
 conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                         const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
@@ -231,24 +243,65 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         img0 += a.dI + c;
     };
 
-    u32x4 xf[KHM][KSM];
+    // XN: where the K value e_lo + 8*h + 16*ks + i (h = 0, 1: the two halves of the wave) sits relative to plan
+    // row 0, unfolded column F*b' of its image: channel plane and unfolded column (the value's folded channel
+    // k = f*C + c lies dw = floor(k / C) columns on).  Wave-uniform, so the table lives in scalar registers:
+    // entry [ks][i] for h = 0 and what h = 1 adds to it.
+    int goff[XN ? KSM : 1][XN ? 8 : 1], goff_hi[XN ? KSM : 1][XN ? 8 : 1];
+    if constexpr (XN) {
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int at[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int k = e_lo + 8 * h + 16 * ks + i;
+                    int dw = k / g.C;
+                    if (k - dw * g.C < 0) --dw;
+                    at[h] = (k - dw * g.C) * (int)a.xP + dw * (int)a.xsB;
+                }
+                goff[ks][i] = at[0];
+                goff_hi[ks][i] = at[1] - at[0];
+            }
+    }
+    // An input fragment: one 16-byte load, or (XN) eight zero-extended 2-byte loads.
+    struct Halves { unsigned d[8]; };
+    using Frag = std::conditional_t<XN, Halves, u32x4>;
+    Frag xf[KHM][KSM];
+    constexpr int LPF = XN ? 8 : 1;  // hand-issued loads per fragment
     auto load_tile = [&]() {
         unsigned wo, ho, img;
         pixel(wo0, ho0, img0, (unsigned)r, wo, ho, img);
         const bool vm = HF ? (cur_tile < a.MT && ho < (unsigned)g.Hout) : m0 + (unsigned)r < (unsigned)g.M;
         const int col0 = (int)wo * g.FC + e0;  // column of K-step 0 inside the input row
         const int pix0 = ((int)(img * (unsigned)g.H + ho) - g.pad_h) * g.in_row + col0;
+        // XN: element offset of (plan row ho - pad_h, unfolded column F*wo, channel 0) of image img
+        const int nc0 = (int)(img * (unsigned)g.C) * (int)a.xP + ((int)ho - g.pad_h) * (int)a.xsA + (int)wo * g.F * (int)a.xsB;
+        // the lane's half of the wave, re-read here so that the per-lane form of the table is not kept in
+        // vector registers across the loop
+        int half = hf;
+        if constexpr (XN) asm volatile("" : "+v"(half));
 #pragma unroll
         for (int kh = 0; kh < KHM; ++kh) {
             const int hi = (int)ho + kh - g.pad_h;
             const bool rv = vm && kh < KH && hi >= 0 && hi < g.H;
 #pragma unroll
             for (int ks = 0; ks < KSM; ++ks) {
-                // in range: row hi exists and the 8-element chunk [col, col+8) lies inside it
+                // in range: row hi exists and the 8-element chunk [col, col+8) lies inside it (chunks do not
+                // straddle the ends of a row: its length and col are multiples of 8)
                 const int col = col0 + 16 * ks;
                 const bool ok = rv && ((ksmask >> ks) & 1u) && col >= 0 && col < g.in_row;
-                const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRangeN;
-                asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(xf[kh][ks]) : "v"(voff), "s"(xr) : "memory");
+                if constexpr (XN) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const unsigned voff = ok ? 2u * (unsigned)(nc0 + kh * (int)a.xsA + goff[ks][i] + half * goff_hi[ks][i]) : kOutOfRangeN;
+                        asm volatile("buffer_load_ushort %0, %1, %2, 0 offen" : "=v"(xf[kh][ks].d[i]) : "v"(voff), "s"(xr) : "memory");
+                    }
+                } else {
+                    const unsigned voff = ok ? 2u * (unsigned)(pix0 + kh * g.in_row + 16 * ks) : kOutOfRangeN;
+                    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(xf[kh][ks]) : "v"(voff), "s"(xr) : "memory");
+                }
             }
         }
     };
@@ -271,6 +324,24 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         }
     };
 
+    // Waits until at most N vector-memory operations are outstanding, and ties the fragment's registers to the wait.
+    auto wait_frag = [&](Frag &f, auto n) {
+        constexpr int N = decltype(n)::value;
+        if constexpr (XN)
+            asm volatile("s_waitcnt vmcnt(%8)"
+                         : "+v"(f.d[0]), "+v"(f.d[1]), "+v"(f.d[2]), "+v"(f.d[3]), "+v"(f.d[4]), "+v"(f.d[5]), "+v"(f.d[6]), "+v"(f.d[7])
+                         : "n"(N) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%1)" : "+v"(f) : "n"(N) : "memory");
+    };
+    auto frag_vec = [&](const Frag &f) {
+        if constexpr (XN) {
+            const u32x4 v = {f.d[0] | (f.d[1] << 16), f.d[2] | (f.d[3] << 16), f.d[4] | (f.d[5] << 16), f.d[6] | (f.d[7] << 16)};
+            return __builtin_bit_cast(Vec, v);
+        } else {
+            return __builtin_bit_cast(Vec, f);
+        }
+    };
     // The fragments in xf times the resident filter, bias included.  STORES_BEHIND: the stores the wave issued
     // after the loads of xf.
     auto multiply = [&](floatx16_t (&acc)[NT], auto stores_behind) {
@@ -285,8 +356,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             // a fragment whose K-step is guarded off is never waited for below, and its registers
             // must not be handed to anything else while its load is still in flight.
 #pragma unroll
-            for (int i = 0; i < KHM * KSM; ++i)
-                asm volatile("s_waitcnt vmcnt(0)" : "+v"(xf[i / KSM][i % KSM]) : : "memory");
+            for (int i = 0; i < KHM * KSM; ++i) wait_frag(xf[i / KSM][i % KSM], std::integral_constant<int, 0>{});
         }
         static_for_n<0, KHM * KSM>([&](auto step) {
             constexpr int idx = decltype(step)::value;
@@ -296,9 +366,9 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 // wave has issued the remaining fragment loads of the tile and then exactly
                 // STORES_BEHIND stores, so the fragment has landed once at most that many operations
                 // are outstanding.  Instances with run-time K guards have drained everything above.
-                constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) + STORES_BEHIND : 0;
-                asm volatile("s_waitcnt vmcnt(%1)" : "+v"(xf[kh][ks]) : "n"(kBehind) : "memory");
-                const Vec xv = __builtin_bit_cast(Vec, xf[kh][ks]);
+                constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) * LPF + STORES_BEHIND : 0;
+                wait_frag(xf[kh][ks], std::integral_constant<int, kBehind>{});
+                const Vec xv = frag_vec(xf[kh][ks]);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
             }
@@ -406,7 +476,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
 static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
 
-template <typename TR, int KHM, int KSM, bool HF>
+template <typename TR, int KHM, int KSM, bool HF, bool XN>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
     NchwArgs a;
@@ -442,6 +512,13 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.x_bytes = (unsigned)((long long)g.N * g.H * g.in_row * (long long)sizeof(T));
     a.y_bytes = (unsigned)((long long)g.N * g.Co * g.Hout * g.out_row * (long long)sizeof(T));
     a.ksteps = ksteps;
+    {
+        // the channels-first image: C planes of (plan rows x unfolded plan columns), transposed for a height fold
+        const long long rows = g.H, cols = (long long)g.Wf * g.F;
+        a.xP = (unsigned)(rows * cols);
+        a.xsA = HF ? 1u : (unsigned)cols;
+        a.xsB = HF ? (unsigned)rows : 1u;
+    }
     // One workgroup per compute unit walks its tiles one after the other (load, multiply, assemble, barrier, write
     // out): it cannot keep the schedule the channels-last kernel keeps, and a workgroup that is behind never sleeps.
     // Offered at 6.8 TB/s it stays on schedule (measured on the headline layer: 79 us unpaced and at 7.35 TB/s,
@@ -454,8 +531,8 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \
     do {                                                                                                     \
-        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF>>()) return e;        \
-        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF><<<blocks, threads, lds_bytes, st>>>(               \
+        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN>>()) return e;    \
+        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN><<<blocks, threads, lds_bytes, st>>>(           \
             g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);                                 \
     } while (0)
     if (exact && g.relu) FC_GO(true, true);
@@ -466,26 +543,30 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     return (int)hipGetLastError();
 }
 
-template <typename TR, bool HF>
+template <typename TR, bool HF, bool XN>
 int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF>(g, ksteps, x, wp, bias, y, st);
-    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN>(g, ksteps, x, wp, bias, y, st);
     return (int)hipErrorInvalidValue;
+}
+
+template <typename TR>
+int launch_layout(const ConvGeom &g, int ksteps, bool height_fold, bool x_nchw, const void *x, const void *wp, const void *bias,
+                  void *y, hipStream_t st) {
+    if (height_fold) return x_nchw ? launch_any<TR, true, true>(g, ksteps, x, wp, bias, y, st)
+                                   : launch_any<TR, true, false>(g, ksteps, x, wp, bias, y, st);
+    if (x_nchw) return (int)hipErrorInvalidValue;  // width folds keep their fold pass (see the head of this file)
+    return launch_any<TR, false, false>(g, ksteps, x, wp, bias, y, st);
 }
 
 }  // namespace
 
-int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, const void *x, const void *w_pack,
-                               const void *bias, void *y, void *stream) {
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, bool x_nchw, const void *x,
+                               const void *w_pack, const void *bias, void *y, void *stream) {
     int ksteps = 0;
     if (!fc_stream_nchw_ok(g, g.band, height_fold, &ksteps)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    if (height_fold) {
-        if (dt == FOLDCONV_F16) return launch_any<F16Traits, true>(g, ksteps, x, w_pack, bias, y, st);
-        if (dt == FOLDCONV_BF16) return launch_any<BF16Traits, true>(g, ksteps, x, w_pack, bias, y, st);
-    } else {
-        if (dt == FOLDCONV_F16) return launch_any<F16Traits, false>(g, ksteps, x, w_pack, bias, y, st);
-        if (dt == FOLDCONV_BF16) return launch_any<BF16Traits, false>(g, ksteps, x, w_pack, bias, y, st);
-    }
+    if (dt == FOLDCONV_F16) return launch_layout<F16Traits>(g, ksteps, height_fold, x_nchw, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_BF16) return launch_layout<BF16Traits>(g, ksteps, height_fold, x_nchw, x, w_pack, bias, y, st);
     return (int)hipErrorInvalidValue;
 }

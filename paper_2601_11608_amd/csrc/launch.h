@@ -76,8 +76,9 @@ int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, 
 // W_out for a width fold, its H_out for a height fold, whose plan is that of the transposed image); false
 // if the geometry does not fit it.
 bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *ksteps);
-int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, const void *x, const void *w_pack,
-                               const void *bias, void *y, void *stream);
+// x_nchw: x is the channels-first input itself (same bytes as x' otherwise), gathered element by element.
+int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, bool x_nchw, const void *x,
+                               const void *w_pack, const void *bias, void *y, void *stream);
 // Streaming kernel with the input tile staged through LDS (dense walks whose K extent fits the registers).
 bool fc_stream_lds_ok(const ConvGeom &g);
 int fc_launch_conv_stream_lds(foldconv_dtype_t dt, const ConvGeom &g, const void *x, const void *w_pack,

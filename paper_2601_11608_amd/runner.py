@@ -116,6 +116,10 @@ class ChannelsFirstLayer:
 
     def forward(self, x, y):
         flags = fc.FLAG_FILTER_PACKED | (fc.FLAG_RELU if self.layer.relu else 0)
+        if self.fused and self.plan.shapes.fold_axis == fc.FOLD_H:
+            # one launch: the kernel reads x and writes y channels-first
+            fc.foldconv_forward(self.plan, x, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW | fc.FLAG_IN_NCHW)
+            return y
         fc.foldconv_fold_input_nchw(self.plan, x, self.x_fold)
         if self.fused:
             fc.foldconv_forward(self.plan, self.x_fold, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW)

@@ -110,6 +110,19 @@ def test_fused_nchw_output(fc, oracle, case, dt):
     got_c = fused(fc, plan, xf, None, b, cws, flags | fc.FLAG_FILTER_COMPACT)
     torch.cuda.synchronize()
     assert torch.equal(got_c.view(torch.int16), want.view(torch.int16))
+    # height folds: the channels-first input read in the same launch (no folded copy): the same bytes again
+    xn = x.cuda().reshape(-1)
+    if axis == fc.FOLD_H:
+        got_in = fused(fc, plan, xn, w_exp, b, ws, flags | fc.FLAG_IN_NCHW)
+        got_in_c = fused(fc, plan, xn, None, b, cws, flags | fc.FLAG_IN_NCHW | fc.FLAG_FILTER_COMPACT)
+        torch.cuda.synchronize()
+        assert not bool(torch.isnan(got_in).any()), "unwritten output elements"
+        assert torch.equal(got_in.view(torch.int16), want.view(torch.int16))
+        assert torch.equal(got_in_c.view(torch.int16), want.view(torch.int16))
+    else:
+        with pytest.raises(fc.FoldconvError) as e:
+            fused(fc, plan, xn, w_exp, b, ws, flags | fc.FLAG_IN_NCHW)
+        assert e.value.status == -3
     if N * Co * H * W <= 1 << 21:
         ph, pw = oracle.axis_pads(KH, KW, pad)
         ref = oracle.conv_direct_nchw(f64(x), f64(w), None if b is None else f64(b.cpu()), ph, pw, relu)
@@ -136,6 +149,10 @@ def test_fused_nchw_headline_layer_full_size(fc, oracle, axis):
     got = fused(fc, plan, xf, w_exp, b, ws, 0)
     torch.cuda.synchronize()
     assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    if axis == "H":
+        got_in = fused(fc, plan, xn.cuda().reshape(-1), w_exp, b, ws, fc.FLAG_IN_NCHW)      # channels-first on both sides
+        torch.cuda.synchronize()
+        assert torch.equal(got_in.view(torch.int16), want.view(torch.int16))
     y = got.cpu().reshape(l.N, l.C_out, l.H, l.W)
     images = [0, 29, 63]
     ref = oracle.conv_direct_nchw(f64(xn[images]), f64(wn), f64(bs[0]), 1, 1)
@@ -219,6 +236,10 @@ def test_fused_nchw_refusals(fc):
     ws = torch.empty(int(s.workspace_bytes), dtype=torch.uint8, device="cuda")
     with pytest.raises(fc.FoldconvError) as e:
         fc.foldconv_forward(plan, x, w, None, y, ws, fc.FLAG_OUT_NCHW | fc.FLAG_KEEP_FOLDED)
+    assert e.value.status == -1
+    # a channels-first input is only read by the kernel that also writes channels-first
+    with pytest.raises(fc.FoldconvError) as e:
+        fc.foldconv_forward(plan, x, w, None, y, ws, fc.FLAG_IN_NCHW)
     assert e.value.status == -1
     # the dense walk needs more K-steps per kh than the fused kernel holds
     with pytest.raises(fc.FoldconvError) as e:
