@@ -23,7 +23,8 @@
 // 16-bit types; 8-byte chunks and one 32x32x8 MFMA for 16-bit layers whose F*C_in
 // is a multiple of 4 only; 16-byte chunks and four chained 32x32x2 MFMAs for fp32
 // (whose K index inside the step is a permutation of the chunk order, the same one
-// for both operands, so the sum is unchanged).  Stores are 16 bytes in every case.
+// for both operands, so the sum is unchanged), or 8-byte chunks and two such MFMAs
+// where that walks fewer structural zeros.  Stores are 16 bytes in every case.
 // paper: Eq. "new_conv_H" (folded convolution), Eq. "bias_construct",
 // Reconstruct step (fused into the store addressing).
 #include <hip/hip_runtime.h>
@@ -95,8 +96,8 @@ conv_stream_kernel(ConvGeom g, StreamArgs a, const typename TR::T *__restrict__ 
     constexpr int EB = (int)sizeof(T);            // bytes per element
     constexpr int E = TR::kPerLane;               // elements per operand chunk (g.epc): a K-step is two chunks,
                                                   // one per half of the wave
-    constexpr int ESH = E == 8 ? 3 : 2;           // log2(E)
-    constexpr int CB = E * EB;                    // bytes per operand chunk: 16, or 8 (16-bit types, E = 4)
+    constexpr int ESH = E == 8 ? 3 : E == 4 ? 2 : 1;  // log2(E)
+    constexpr int CB = E * EB;                    // bytes per operand chunk: 16, or 8 (16-bit types with E = 4, fp32 with E = 2)
     using XV = std::conditional_t<CB == 16, u32x4, u32x2>;  // an input fragment as loaded
     static_assert(sizeof(Vec) == CB && (CB == 16 || CB == 8), "operand chunks of 8 or 16 bytes");
     constexpr int EO = 16 / EB;                   // elements per 16-byte chunk of the stored output
@@ -453,5 +454,6 @@ int fc_launch_conv_stream(foldconv_dtype_t dt, const ConvGeom &g, const void *x,
     if (dt == FOLDCONV_F16 && g.epc == 4) return launch_shape<F16HalfTraits>(g, sh, x, w_pack, bias, y, st);
     if (dt == FOLDCONV_BF16 && g.epc == 4) return launch_shape<BF16HalfTraits>(g, sh, x, w_pack, bias, y, st);
     if (dt == FOLDCONV_F32 && g.epc == 4) return launch_shape<F32ChunkTraits>(g, sh, x, w_pack, bias, y, st);
+    if (dt == FOLDCONV_F32 && g.epc == 2) return launch_shape<F32PairTraits>(g, sh, x, w_pack, bias, y, st);
     return (int)hipErrorInvalidValue;
 }

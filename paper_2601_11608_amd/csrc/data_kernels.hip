@@ -145,7 +145,7 @@ template <int N> struct ChunkOf;
 template <> struct ChunkOf<16> { typedef u32x4 type; };
 template <> struct ChunkOf<8> { typedef u32x2 type; };
 
-template <typename U, int E>  // uint16_t: chunks of 8 or 4 rows; uint32_t (fp32): chunks of 4
+template <typename U, int E>  // uint16_t: chunks of 8 or 4 rows; uint32_t (fp32): chunks of 4 or 2
 __global__ void __launch_bounds__(kThreads)
 pack_filter_kernel(const U *__restrict__ we, typename ChunkOf<E * sizeof(U)>::type *__restrict__ pack, int KH, int kwin, int NCo) {
     const int q_per_kh = kwin / E;
@@ -527,8 +527,8 @@ int fc_launch_crop_channels(const foldconv_plan_s *p, const void *y_pad, void *y
     return last_error();
 }
 
-// the operand chunks the packers write: 8 or 4 elements of a 16-bit type, 4 of fp32
-static bool chunk_ok(const ConvGeom &g) { return (g.eb == 2 && (g.epc == 8 || g.epc == 4)) || (g.eb == 4 && g.epc == 4); }
+// the operand chunks the packers write: 8 or 4 elements of a 16-bit type, 4 or 2 of fp32
+static bool chunk_ok(const ConvGeom &g) { return (g.eb == 2 && (g.epc == 8 || g.epc == 4)) || (g.eb == 4 && (g.epc == 4 || g.epc == 2)); }
 
 int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w_pack, void *stream) {
     if (elem_bytes != g.eb || !chunk_ok(g) || g.kwin % g.epc != 0) return (int)hipErrorInvalidValue;
@@ -539,8 +539,10 @@ int fc_launch_pack(const ConvGeom &g, int elem_bytes, const void *w_exp, void *w
         pack_filter_kernel<uint16_t, 8><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
     else if (elem_bytes == 2)
         pack_filter_kernel<uint16_t, 4><<<grid, kThreads, 0, st>>>((const uint16_t *)w_exp, (u32x2 *)w_pack, g.KH, g.kwin, g.NCo);
-    else
+    else if (g.epc == 4)
         pack_filter_kernel<uint32_t, 4><<<grid, kThreads, 0, st>>>((const uint32_t *)w_exp, (u32x4 *)w_pack, g.KH, g.kwin, g.NCo);
+    else
+        pack_filter_kernel<uint32_t, 2><<<grid, kThreads, 0, st>>>((const uint32_t *)w_exp, (u32x2 *)w_pack, g.KH, g.kwin, g.NCo);
     return last_error();
 }
 
@@ -555,8 +557,11 @@ int fc_launch_compact(const ConvGeom &g, int elem_bytes, const void *w, void *w_
     else if (elem_bytes == 2)
         compact_filter_kernel<uint16_t, 4><<<grid, kThreads, 0, st>>>((const uint16_t *)w, (u32x2 *)w_compact, g.KH,
                                                                       g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
-    else
+    else if (g.epc == 4)
         compact_filter_kernel<uint32_t, 4><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (u32x4 *)w_compact, g.KH,
+                                                                      g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
+    else
+        compact_filter_kernel<uint32_t, 2><<<grid, kThreads, 0, st>>>((const uint32_t *)w, (u32x2 *)w_compact, g.KH,
                                                                       g.KW * g.C, g.Co, g.cJ, g.cgcd, total);
     return last_error();
 }

@@ -33,8 +33,9 @@ struct ConvGeom {
     int C;       // original input channels (band arithmetic)
     int F, KH, KW, pad_h, pad_w;
     int epc;     // elements per operand chunk (what a lane loads of x' and of the filter per K-step half):
-                 // 8 for the 16-bit types (16 bytes), 4 for fp32 (16 bytes), and 4 for a 16-bit layer whose
-                 // F*C_in is a multiple of 4 but not of 8 (8-byte chunks, streaming kernel only)
+                 // 8 for the 16-bit types (16 bytes), 4 for fp32 (16 bytes); 8-byte chunks on the streaming kernel:
+                 // 4 for a 16-bit layer whose F*C_in is a multiple of 4 but not of 8, 2 for an fp32 layer
+                 // that walks fewer structural zeros that way (or whose F*C_in is a multiple of 2 only)
     int eb;      // bytes per element; stored output chunks are always 16 bytes = 16/eb elements
     int e_min, e_max;  // dense window of extended channels, [e_min, e_max)
     int kwin;          // e_max - e_min = KW'*FC = filter rows per kh
@@ -79,16 +80,20 @@ FC_HD void fc_band_window(const ConvGeom &g, int n_lo, int n_hi, int align, int 
 // E is a template argument (it must equal g.epc) so that the kernels divide by shifting.
 template <int E>
 FC_HD long long fc_compact_chunk(const ConvGeom &g, int kh, int q, int n) {
-    static_assert(E == 4 || E == 8, "chunks of 4 or 8 elements");
-    constexpr int SH = E == 8 ? 3 : 2;
+    static_assert(E == 2 || E == 4 || E == 8, "chunks of 2, 4 or 8 elements");
+    constexpr int SH = E == 8 ? 3 : E == 4 ? 2 : 1;
     const int slot = n / g.Co, co = n - slot * g.Co;
     const int a = (slot - g.pad_w) * g.C - g.e_min;  // >= 0 because e_min <= -p*C_in
     const int j = q - (a >> SH);
     if (j < 0 || j >= g.cJ) return -1;
     return ((long long)(((a & (E - 1)) / g.cgcd) * g.KH + kh) * g.cJ + j) * g.Co + co;
 }
-// gcd(c, epc) for epc = 4 or 8
-FC_HD int fc_gcd_chunk(int c, int epc) { return (c % 8 == 0 && epc == 8) ? 8 : (c % 4 == 0) ? 4 : (c % 2 == 0) ? 2 : 1; }
+// gcd(c, epc) for epc = 2, 4 or 8
+FC_HD int fc_gcd_chunk(int c, int epc) {
+    int d = epc;
+    while (c % d != 0) d /= 2;
+    return d;
+}
 FC_HD int fc_compact_phases(const ConvGeom &g) { return g.epc / g.cgcd; }
 
 // How the persistent streaming kernels deal their 32-pixel M tiles to the XCDs (8 on MI355X; workgroup

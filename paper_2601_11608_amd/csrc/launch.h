@@ -18,7 +18,7 @@ struct StreamShape {
 // Compiled instances of the streaming kernel: X(NT, max KH, max K-steps per kh, workgroups per CU).
 // Filter fragments cost 4*NT*KH*ksteps registers per lane, which bounds the list.
 #define FC_STREAM_INSTANCES(X) \
-    X(2, 1, 1, 2) X(2, 3, 1, 2) X(2, 5, 1, 2) X(2, 1, 2, 2) X(2, 3, 2, 2) X(2, 3, 4, 2) X(2, 1, 6, 2) X(2, 3, 9, 1) \
+    X(2, 1, 1, 2) X(2, 3, 1, 2) X(2, 5, 1, 2) X(2, 1, 2, 2) X(2, 3, 2, 2) X(2, 3, 3, 2) X(2, 3, 4, 2) X(2, 1, 6, 2) X(2, 3, 9, 1) \
     X(4, 1, 2, 2) X(4, 3, 2, 2)
 bool fc_stream_shape(const ConvGeom &g, int band, StreamShape *out);
 

@@ -8,7 +8,7 @@
 //   16-bit types in 8-byte chunks, v_mfma_f32_32x32x8_{f16,bf16} (F16HalfTraits, BF16HalfTraits): the same with
 //     four K values per lane, k = k0 + 4*(l/32) + j, j = 0..3;
 //   fp32, v_mfma_f32_32x32x2_f32: one element each, k = k0 + l/32 (the element-gather kernel), or
-//     four per lane used by four MFMAs in turn (F32ChunkTraits, the streaming kernel).
+//     four (two) per lane used by four (two) MFMAs in turn (F32ChunkTraits, F32PairTraits: the streaming kernel).
 // Accumulator register r (0..15) of lane l holds
 //   D[n0 + 8*(r/4) + 4*(l/32) + r%4][m0 + l%32],
 // i.e. four consecutive output channels of one pixel per register quad.
@@ -23,6 +23,7 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef short shortx4_t __attribute__((ext_vector_type(4)));
 typedef float floatx16_t __attribute__((ext_vector_type(16)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
 
 struct F16Traits {
     using T = _Float16;
@@ -89,6 +90,23 @@ struct F32ChunkTraits {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], c, 0, 0, 0);
     }
     // the product when only element 0 of a and b is non-zero (the rank-1 bias term): one MFMA instead of four
+    static __device__ __forceinline__ floatx16_t mfma_k0(Vec a, Vec b, floatx16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ T from_float(float v) { return v; }
+};
+
+// fp32 in 8-byte chunks of two K values: a K-step of 4 is two MFMAs.  Half the alignment loss of the 16-byte
+// chunks on a narrow band (a 9-wide band costs 12 K values instead of 16), twice the load instructions.
+struct F32PairTraits {
+    using T = float;
+    using Vec = floatx2_t;
+    static constexpr int kPerLane = 2;
+    static constexpr int kStep = 4;
+    static __device__ __forceinline__ floatx16_t mfma(Vec a, Vec b, floatx16_t c) {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], c, 0, 0, 0);
+    }
     static __device__ __forceinline__ floatx16_t mfma_k0(Vec a, Vec b, floatx16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], c, 0, 0, 0);
     }

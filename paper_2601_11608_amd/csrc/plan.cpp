@@ -80,6 +80,8 @@ static double walk_flops(int plan_kernel, ConvGeom g, int band, foldconv_dtype_t
 //   * filter term: the expanded filter read at 1 TB/s (every wave fetches its own fragments; a larger
 //     F buys nothing once F*C_in is aligned, and its F^2 larger filter is not free);
 //   * overhead: 4.5 us (streaming), 8 us (tiled), 10 us (gather) per launch.
+constexpr double kStreamFp32Rate = 0.08e15;  // issued fp32 MFMA flops per second the streaming kernel sustains
+
 static double model_seconds(const foldconv_shapes_t &s, int wave_columns, bool half_chunks) {
     const double x = (double)s.x_bytes, y = (double)s.y_bytes;
     const double wf = s.prefer_compact ? (double)s.filter_compact_bytes : (double)s.w_exp_bytes;
@@ -90,7 +92,7 @@ static double model_seconds(const foldconv_shapes_t &s, int wave_columns, bool h
         overhead = 4.5e-6;
         // fp32: K = 2 MFMAs, 157 TFLOP/s peak; 8-byte operand chunks: K = 8 MFMAs at half the rate of K = 16
         // (0.19 PFLOP/s measured on the guarded nine-step instance, 0.35 and more on the exact two-step one)
-        rate = s.dtype == FOLDCONV_F32 ? 0.08e15 : half_chunks ? 0.33e15 : 1.0e15;
+        rate = s.dtype == FOLDCONV_F32 ? kStreamFp32Rate : half_chunks ? 0.33e15 : 1.0e15;
         const double cols = (double)((s.Co_fold + wave_columns - 1) / wave_columns) * wave_columns;
         y_eff = y * cols / (double)s.Co_fold;
     } else if (s.conv_kernel == FC_KERNEL_TILED) {
@@ -176,10 +178,30 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     g.e_min = (int)(d_min * FC); g.e_max = (int)((d_max + 1) * FC); g.kwin = g.e_max - g.e_min;
     g.in_row = (int)(Wf * FC); g.out_row = (int)(W_out * C_out); g.M = M;
     g.eb = eb;
+    auto set_chunk = [&](ConvGeom &gg, int epc) {
+        gg.epc = epc;
+        gg.cgcd = fc_gcd_chunk(C_in, epc);
+        gg.cJ = (epc - gg.cgcd + KW * C_in + epc - 1) / epc;
+    };
     // operand chunks of 16 bytes; 8-byte chunks for a 16-bit layer whose folded channel count allows no more
-    g.epc = (eb == 2 && FC % 8 != 0 && FC % 4 == 0) ? 4 : 16 / eb;
-    g.cgcd = fc_gcd_chunk(C_in, g.epc);
-    g.cJ = (g.epc - g.cgcd + KW * C_in + g.epc - 1) / g.epc;
+    set_chunk(g, (eb == 2 && FC % 8 != 0 && FC % 4 == 0) ? 4 : 16 / eb);
+    if (eb == 4) {
+        // A large fp32 layer is bound by its MFMAs (K = 2 each), and there the chunk that walks fewer structural
+        // zeros wins: 8-byte chunks round the band of an output slot to 2 channels and K-steps of 4 instead of
+        // 4 and 8 (the headline shape in fp32: 174 us against 191 us).  Layers that the model's rates put on the
+        // memory side, the launch-bound ones included, keep 16-byte chunks: fewer load instructions.
+        ConvGeom g2 = g;
+        set_chunk(g2, 2);
+        const bool s4 = fc_choose_kernel(g, dtype) == FC_KERNEL_STREAM;
+        const bool s2 = fc_choose_kernel(g2, dtype) == FC_KERNEL_STREAM;
+        if (s2 && !s4) {
+            g = g2;
+        } else if (s2) {
+            const double f4 = walk_flops(FC_KERNEL_STREAM, g, 1, dtype), f2 = walk_flops(FC_KERNEL_STREAM, g2, 1, dtype);
+            const double t_mem = ((double)s.x_bytes + (double)s.y_bytes) / 6.2e12 + 4.5e-6;
+            if (f2 < f4 && f4 / kStreamFp32Rate > t_mem) g = g2;
+        }
+    }
 
     // Zero-padded reference problem: F = 1, every pixel C_pad channels.
     ConvGeom &q = p->padc;
@@ -232,7 +254,7 @@ extern "C" int foldconv_plan(int N, int H, int W, int C_in, int C_out, int KH, i
     s.issued_flops_dense = walk_flops(s.conv_kernel, g, 0, dtype);
     s.issued_flops_band = walk_flops(s.conv_kernel, g, 1, dtype);
     s.issued_flops_padded = walk_flops(s.padded_kernel, q, 1, dtype);
-    s.model_seconds = model_seconds(s, fc_band_tile_n(s.conv_kernel, g), g.epc * eb == 8);
+    s.model_seconds = model_seconds(s, fc_band_tile_n(s.conv_kernel, g), eb == 2 && g.epc == 4);
 
     *out = p;
     return FOLDCONV_OK;

@@ -25,10 +25,10 @@ int max_ksteps(ConvGeom g, int band, int cols) {
 // Conditions shared by the vector kernels.
 static bool vector_ok(const ConvGeom &g) {
     // Operand side: folded channels and the filter window in multiples of the operand chunk (8 elements of a
-    // 16-bit type, or 4 where F*C_in allows no more; 4 of fp32).  Output side: columns and stored rows in
+    // 16-bit type, or 4 where F*C_in allows no more; 4 or 2 of fp32).  Output side: columns and stored rows in
     // multiples of a 16-byte chunk.
     const int E = g.epc, EO = 16 / g.eb;
-    if (!((g.eb == 2 && (E == 8 || E == 4)) || (g.eb == 4 && E == 4))) return false;
+    if (!((g.eb == 2 && (E == 8 || E == 4)) || (g.eb == 4 && (E == 4 || E == 2)))) return false;
     if (g.FC % E != 0 || g.kwin % E != 0 || g.NCo % EO != 0 || g.out_row % EO != 0) return false;
     // 32-bit byte offsets into x and into the packed filter, 32-bit chunk index into y.
     const long long eb = g.eb;

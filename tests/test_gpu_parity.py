@@ -406,15 +406,19 @@ def test_random_geometries(fc, oracle, chunk, dt):
 
 
 @pytest.mark.parametrize("case", [(4, 64, 224, 3, 64, 3, 3, 1, 16, True, False),     # the headline layer's shape, 4 images
+                                  (16, 64, 224, 3, 64, 3, 3, 1, 16, True, True),      # 16 images: bound by its MFMAs, 8-byte chunks
                                   (2, 40, 48, 12, 48, 3, 3, 1, 4, False, True),       # c3-like: several K-steps per kh
                                   (3, 1, 4000, 1, 64, 1, 9, 4, 32, True, False),      # 1-D, one input channel
-                                  (1, 30, 64, 6, 10, 3, 3, 1, 2, True, True)],        # F*C_out = 20: cropped columns
+                                  (1, 30, 64, 6, 10, 3, 3, 1, 2, True, True),         # F*C_out = 20: cropped columns
+                                  (2, 24, 30, 3, 16, 3, 3, 1, 2, True, False),        # F*C_in = 6: 8-byte chunks only
+                                  (2, 20, 24, 16, 32, 3, 3, 1, 1, False, True)],      # unfolded, C_in = 16: 16-byte chunks
                          ids=lambda c: "x".join(map(str, c[:9])))
 def test_fp32_layers_on_the_streaming_kernel(fc, oracle, case):
-    """fp32 tensors whose folded pixels are whole 16-byte chunks (F*C_in a multiple of 4) run the
-    streaming kernel: steps of 8 K values as four MFMAs of K = 2, fp32 all the way (paper, appendix
-    listing: the fp32 setting of its equivalence check).  Every walk and the zero-padded reference
-    against the oracle, rel-L2 and element by element."""
+    """fp32 tensors whose folded pixels are whole 8- or 16-byte chunks (F*C_in a multiple of 2 or 4)
+    run the streaming kernel: steps of 4 or 8 K values as two or four MFMAs of K = 2, whichever walks
+    fewer structural zeros, fp32 all the way (paper, appendix listing: the fp32 setting of its
+    equivalence check).  Every walk and the zero-padded reference against the oracle, rel-L2 and
+    element by element."""
     N, H, W, C, Co, KH, KW, pad, F, hb, relu = case
     dt = "f32"
     x = draw((N, H, W, C), dt, 71)

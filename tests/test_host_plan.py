@@ -238,9 +238,17 @@ def test_compact_filter_size(fc):
             assert s.filter_compact_bytes < s.w_exp_bytes / 3
     s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float16").shapes
     assert (s.w_exp_bytes, s.filter_compact_bytes) == (884736, 49152)
-    # fp32 on the streaming kernel: chunks of 4 rows, 4/gcd(C_in,4) copies
+    # fp32 on the streaming kernel.  A small layer: chunks of 4 rows (16 bytes), 4/gcd(C_in,4) copies.  A large
+    # layer with C_in = 3 (bound by its MFMAs): chunks of 2 rows (8 bytes, fewer structural zeros walked),
+    # 2/gcd(C_in,2) copies.  C_in = 12: chunks of 4 rows, one copy
     s = fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 8, "float32").shapes
     assert s.conv_kernel == 2 and s.filter_compact_bytes == (4 * 3 * ((4 - 1 + 9 + 3) // 4) * 16 * 16 + 255) // 256 * 256
+    s = fc.foldconv_plan(64, 224, 224, 3, 64, 3, 3, 1, 16, "float32").shapes
+    assert s.conv_kernel == 2 and s.filter_compact_bytes == (2 * 3 * ((2 - 1 + 9 + 1) // 2) * 64 * 8 + 255) // 256 * 256
+    s = fc.foldconv_plan(32, 112, 112, 12, 48, 3, 3, 1, 4, "float32").shapes
+    assert s.conv_kernel == 2 and s.filter_compact_bytes == (1 * 3 * ((4 - 4 + 36 + 3) // 4) * 48 * 16 + 255) // 256 * 256
+    # F*C_in = 6: a multiple of 2 only
+    assert fc.foldconv_plan(1, 32, 32, 3, 16, 3, 3, 1, 2, "float32").shapes.conv_kernel == 2
     # a 16-bit layer whose F*C_in is a multiple of 4 only: streaming kernel, 8-byte chunks of 4 rows
     s = fc.foldconv_plan(4, 60, 300, 3, 64, 3, 3, 1, 4, "float16").shapes
     assert s.conv_kernel == 2 and s.filter_compact_bytes == (4 * 3 * ((4 - 1 + 9 + 3) // 4) * 64 * 8 + 255) // 256 * 256

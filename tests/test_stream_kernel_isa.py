@@ -61,7 +61,7 @@ def test_hand_counted_waits_cover_every_fragment(asm):
         m = re.search(r"TraitsLi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELb([01])ELb([01])E", name)
         nt, khm, ksm, exact = int(m.group(1)), int(m.group(2)), int(m.group(3)), m.group(5) == "1"
         # 16-byte store passes per 32-row tile of 32*nt columns: 8 elements per piece, 4 for fp32
-        passes = (4 if "F32ChunkTraits" in name else 2) * nt
+        passes = (4 if "F32" in name else 2) * nt
         lines = loop_lines(asm, name)
         loads = [i for i, l in enumerate(lines) if re.match(r"buffer_load_dwordx[24] ", l)]   # dwordx2: 8-byte operand chunks
         assert len(loads) == khm * ksm, name
