@@ -26,6 +26,13 @@
 // columns of a channel row: whole 128-byte lines (half lines, written tile by tile, cost a
 // quarter of the launch).
 //
+// HQ instances (height folds whose F*C_out is a multiple of 128) go one step further: a workgroup owns half of
+// the columns (the slots of one half of the fold) for its whole life and assembles *four* tiles, 128 plan rows, in
+// the same LDS before writing them out, its waves forming two groups that compute two of the four tiles each.
+// Sixteen neighbouring lanes then store 256 consecutive bytes of a channel row.  A stand-alone stream of these
+// store patterns over the 411 MB output of the headline layer takes 100 us with 128-byte runs and 83 us with
+// 256-byte runs (68 us with the 1 KB runs of the width fold): the store pattern is what bounds this kernel.
+//
 // XN instances (height folds) read a channels-first input as well: the folded pixel's channel f*C_in + c of
 // plan row a is x[n][c][F*b'+f][a], so a lane's fragment of eight K-contiguous values is gathered with eight
 // 2-byte loads (one register each, paired up after they land: on this GPU a 16-bit load into one half of a
@@ -95,20 +102,28 @@ __device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigne
 }
 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
-template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN>
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN, bool HQ>
 __global__ void __launch_bounds__(1024, 1)
 conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                         const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
     using T = typename TR::T;
     using Vec = typename TR::Vec;
     constexpr int NT = 2, COLS = 64;
-    extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];  // two tiles of 32 * pitch bytes
+    static_assert(HF || !HQ, "quads are a height-fold layout");
+    extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];  // two (HQ: four) tiles of 32 * pitch bytes
 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int r = lane & 31, hf = lane >> 5;
-    const int n_lo = wave * COLS;
+    // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).  HQ: two workgroups on
+    // the same XCD, one per half of the columns, walk the same quads.
+    const unsigned xcd = blockIdx.x % a.deal.parts, wg = blockIdx.x / a.deal.parts;
+    const int col_half = HQ ? (int)(wg & 1u) : 0;
+    const int col0 = col_half * (g.NCo >> 1);            // first column the workgroup's LDS tiles hold
+    const int wpg = HQ ? (int)(blockDim.x >> 7) : 1;     // HQ: waves per tile group = (F*C_out / 2) / 64
+    const int tg = HQ ? wave / wpg : 0;                  // HQ: the wave computes tiles 2*tg and 2*tg + 1 of a quad
+    const int n_lo = HQ ? col0 + (wave - tg * wpg) * COLS : wave * COLS;
     const int KH = EXACT ? KHM : g.KH, KS = EXACT ? KSM : a.ksteps;
 
     int e_lo, e_hi;
@@ -171,32 +186,35 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     //      channels [4*co4, 4*co4+4): 32 * (F/8) threads per channel quadruple, C_out/4 quadruples.
     //      HF: pixels [8*da8, 8*da8+8) of the tile pair (da8 < 4: first tile, else second), slots hg and
     //      hg + F/2 in turn, channels [4*co4, 4*co4+4); da8 runs fastest over the lanes, so eight lanes
-    //      store 128 consecutive bytes of a channel row.
+    //      store 128 consecutive bytes of a channel row.  HQ: da8 < 16 over the four tiles of the quad (sixteen
+    //      lanes store 256 consecutive bytes), slots hg and hg + F/4 of the workgroup's half of the fold.
     const int g8n = HF ? 1 : g.F >> 3;
     const int per_c4 = 32 * g8n;
     const int c4n = g.Co >> 2;
-    const int co4 = HF ? (t >> 3) % c4n : t / per_c4;
+    constexpr int DAB = HQ ? 4 : 3;  // log2 of the 8-pixel groups along the plan rows of a pair or quad
+    const int co4 = HF ? (t >> DAB) % c4n : t / per_c4;
     const int sp = HF ? 0 : (t - co4 * per_c4) / g8n;
     const int sg8 = HF ? 0 : (t - co4 * per_c4) - sp * g8n;
-    const int da8 = HF ? t & 7 : 0;
-    const int hg = HF ? t / (8 * c4n) : 0;  // below F/2: the block has F*C_out threads
-    // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel, + (F/2) * C_out * 2 for the second slot
+    const int da8 = HF ? t & ((1 << DAB) - 1) : 0;
+    const int hg = HF ? t / ((1 << DAB) * c4n) : 0;  // below F/2 (HQ: F/4): the block has F*C_out threads
+    const int slot_step = HQ ? g.F >> 2 : g.F >> 1;   // HF: the thread's second slot lies this far from its first
+    // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel, + slot_step * C_out * 2 for the second slot
     const int rd_off = HF ? ((da8 >> 2) * 32 + 8 * (da8 & 3)) * a.pitch + (hg * g.Co + 4 * co4) * 2
                           : sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;
     const int rd_step = HF ? a.pitch : g.Co * 2;
     // bytes per channel plane: image H_out x W_out (W fold: Hout x out_row; HF: out_row x Hout, the plan is transposed)
     const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;
 
-    // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).
-    const unsigned xcd = blockIdx.x % a.deal.parts, wg = blockIdx.x / a.deal.parts;
-    const unsigned t_first = fc_deal_first_tile(a.deal, xcd, wg);  // the workgroup's first tile
+    const unsigned t_first = fc_deal_first_tile(a.deal, xcd, HQ ? wg >> 1 : wg);  // the workgroup's first tile
 
     // The workgroup's current tile.  W fold: 32 consecutive folded pixels from m0 = (img0, ho0, wo0), advanced
     // incrementally.  HF: tile pair `tile` = (img0 * tiles_ab + pair) * Wf_out + wo0 (folded column fastest:
     // consecutive pairs share their 64 input rows); its half `sub` holds plan rows [ho0, ho0 + 32),
     // ho0 = 64 * pair + 32 * sub.  A half that starts at or beyond Hout reads zeros and stores nothing.
+    // HQ: the same with quads of 128 plan rows; the wave's tiles are 2*tg + sub: ho0 = 128 * quad + 32 * (2*tg + sub).
     unsigned m0 = t_first * 32u;
     unsigned wo0, ho0, img0;
+    unsigned row0 = 0;  // HF: first plan row of the pair or quad
     unsigned cur_tile = t_first;
     auto place = [&](unsigned tile, unsigned sub) {
         if (HF) {
@@ -206,7 +224,8 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             const unsigned rb = tl / (unsigned)g.Wf_out;  // (image, pair)
             wo0 = tl - rb * (unsigned)g.Wf_out;
             img0 = rb / a.tiles_ab;
-            ho0 = (rb - img0 * a.tiles_ab) * 64u + 32u * sub;
+            row0 = (rb - img0 * a.tiles_ab) * (HQ ? 128u : 64u);
+            ho0 = row0 + 32u * (HQ ? 2u * (unsigned)tg + sub : sub);
         } else {
             wo0 = m0 % (unsigned)g.Wf_out;
             const unsigned rowid = m0 / (unsigned)g.Wf_out;
@@ -389,7 +408,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 }
                 const int n = n_lo + 32 * nt + 8 * q + 4 * hf;
                 const int slot8 = (n / g.Co) >> 3;
-                *reinterpret_cast<u32x2 *>(tb + r * a.pitch + n * 2 + slot8 * a.skew) = pk;
+                *reinterpret_cast<u32x2 *>(tb + r * a.pitch + (n - col0) * 2 + slot8 * a.skew) = pk;
             }
     };
     // Eight 8-byte reads at src (four channels of eight neighbouring slots or pixels), regrouped into four
@@ -415,11 +434,11 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         // per thread, and a second barrier before the next pair's first half overwrites buffer 0.  The input
         // of the half after the current one is always in flight: behind the loads of a first half lie the
         // eight stores of the pair before it, behind those of a second half none.
-        unsigned char *const tb0 = tile_lds, *const tb1 = tile_lds + 32 * a.pitch;
+        unsigned char *const tb0 = tile_lds + (HQ ? 2 * tg : 0) * (32 * a.pitch), *const tb1 = tb0 + 32 * a.pitch;
         for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
             floatx16_t acc[NT];
             multiply(acc, std::integral_constant<int, 8>{});
-            const unsigned cur_wo0 = wo0, cur_ho0 = ho0, cur_img0 = img0;  // first half: ho0 = 64 * pair
+            const unsigned cur_wo0 = wo0, cur_ho0 = row0, cur_img0 = img0;  // first plan row of the pair or quad
             place(mt, 1);
             load_tile();
             __syncthreads();  // every wave has finished reading the previous pair out of both buffers
@@ -436,12 +455,12 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             const unsigned w0 = cur_ho0 + 8u * (unsigned)da8;  // first image column of the piece
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                const unsigned slot = (unsigned)hg + (unsigned)half * ((unsigned)g.F >> 1);
+                const unsigned slot = (unsigned)(col_half * (g.F >> 1) + hg + half * slot_step);
                 const unsigned h = cur_wo0 * (unsigned)g.F + slot;  // image row
                 const bool ok = h < (unsigned)g.out_row && w0 < (unsigned)g.Hout;  // Hout % 8 == 0: a piece is whole or absent
                 const unsigned off0 =
                     2u * (((cur_img0 * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.out_row + h) * (unsigned)g.Hout + w0);
-                write_out(tile_lds + rd_off + half * ((g.F >> 1) * g.Co * 2), off0, ok);
+                write_out(tile_lds + rd_off + half * (slot_step * g.Co * 2), off0, ok);
             }
         }
     } else {
@@ -476,7 +495,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
 static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
 
-template <typename TR, int KHM, int KSM, bool HF, bool XN>
+template <typename TR, int KHM, int KSM, bool HF, bool XN, bool HQ>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
     NchwArgs a;
@@ -484,25 +503,26 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
         // a thread of the write-out reads pixels 8 rows apart and eight neighbouring lanes read pixels 8k .. 8k+7
         // of the pair: with a pitch of 8 bytes (mod 32) the lanes of a wave spread over all banks in both phases
         a.skew = 0;
-        a.pitch = g.NCo * 2 + 8;
+        a.pitch = (HQ ? g.NCo / 2 : g.NCo) * 2 + 8;  // HQ: a workgroup's tiles hold half of the columns
     } else {
         const int g8n = g.F / 8;
         a.skew = g8n > 1 ? 256 / g8n : 0;
         if (a.skew % 8 != 0) a.skew = 8;
         a.pitch = g.NCo * 2 + g8n * a.skew + 8;
     }
-    const unsigned lds_bytes = 2u * 32u * (unsigned)a.pitch;
+    const unsigned lds_bytes = (HQ ? 4u : 2u) * 32u * (unsigned)a.pitch;
     const unsigned threads = (unsigned)g.NCo;  // one wave per 64 columns
     // workgroups resident per compute unit: 16 waves at the register budget of the launch bounds, 160 KB of LDS
     unsigned per_cu = 1024u / threads;
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
-    a.tiles_ab = (unsigned)((g.Hout + 63) / 64);
+    a.tiles_ab = HQ ? (unsigned)((g.Hout + 127) / 128) : (unsigned)((g.Hout + 63) / 64);
     a.MT = HF ? (unsigned)((long long)g.N * a.tiles_ab * g.Wf_out) : (unsigned)((g.M + 31) / 32);
     FcDevice dev;
     if (int e = fc_device(&dev)) return e;
     // HF: the Wf_out tiles of a row block share all their input rows; keep them in one chunk (one L2)
-    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu, g.KH, HF ? 8 * g.Wf_out : g.Wf_out);
+    // HQ: two workgroups (the two halves of the columns) walk the same quads: half as many walkers
+    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu / (HQ ? 2u : 1u), g.KH, HF ? 8 * g.Wf_out : g.Wf_out);
     const long long S = 32LL * a.deal.stride, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
@@ -527,12 +547,12 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.pace = g.unpaced ? 0u
                        : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride,
                                        dev.wall_khz, 6.8e12);
-    const unsigned blocks = a.deal.J * a.deal.parts;
+    const unsigned blocks = a.deal.J * a.deal.parts * (HQ ? 2u : 1u);
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \
     do {                                                                                                     \
-        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN>>()) return e;    \
-        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN><<<blocks, threads, lds_bytes, st>>>(           \
+        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ>>()) return e; \
+        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ><<<blocks, threads, lds_bytes, st>>>(       \
             g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);                                 \
     } while (0)
     if (exact && g.relu) FC_GO(true, true);
@@ -543,20 +563,27 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     return (int)hipGetLastError();
 }
 
-template <typename TR, bool HF, bool XN>
+template <typename TR, bool HF, bool XN, bool HQ>
 int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN>(g, ksteps, x, wp, bias, y, st);
-    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN, HQ>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN, HQ>(g, ksteps, x, wp, bias, y, st);
     return (int)hipErrorInvalidValue;
 }
 
 template <typename TR>
 int launch_layout(const ConvGeom &g, int ksteps, bool height_fold, bool x_nchw, const void *x, const void *wp, const void *bias,
                   void *y, hipStream_t st) {
-    if (height_fold) return x_nchw ? launch_any<TR, true, true>(g, ksteps, x, wp, bias, y, st)
-                                   : launch_any<TR, true, false>(g, ksteps, x, wp, bias, y, st);
+    if (height_fold) {
+        // quads of four tiles where the two halves of the fold are whole waves, a thread of the write-out has its
+        // two slots and the image is wide enough for 256-byte runs to exist
+        const bool quads = g.NCo % 128 == 0 && g.F % 4 == 0 && g.Hout > 64;
+        if (quads) return x_nchw ? launch_any<TR, true, true, true>(g, ksteps, x, wp, bias, y, st)
+                                 : launch_any<TR, true, false, true>(g, ksteps, x, wp, bias, y, st);
+        return x_nchw ? launch_any<TR, true, true, false>(g, ksteps, x, wp, bias, y, st)
+                      : launch_any<TR, true, false, false>(g, ksteps, x, wp, bias, y, st);
+    }
     if (x_nchw) return (int)hipErrorInvalidValue;  // width folds keep their fold pass (see the head of this file)
-    return launch_any<TR, false, false>(g, ksteps, x, wp, bias, y, st);
+    return launch_any<TR, false, false, false>(g, ksteps, x, wp, bias, y, st);
 }
 
 }  // namespace

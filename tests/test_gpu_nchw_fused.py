@@ -80,6 +80,12 @@ FUSED_H = [
     (2, 2, 64, 25, 24, 3, 2, 0, 8, False, False),     # KW = 2 (the plan's KH): the guarded instance; VALID, W_out = 24, H_out = 62
     (2, 1, 32, 18, 16, 3, 3, 0, 8, True, False),      # VALID: H_out = 30 is not a multiple of F: the last slots are dropped; W_out = 16
     (3, 1, 16, 8, 8, 1, 1, 0, 16, True, False),       # one folded column, one row block
+    # image wider than 64 columns and F*C_out a multiple of 128: quads of four tiles, 256-byte store runs
+    (2, 3, 48, 136, 64, 3, 3, 1, 16, True, True),     # 16 waves; a full quad and one of 8 columns
+    (1, 1, 64, 200, 32, 3, 3, 1, 8, False, True),     # 4 waves: two per tile group; 128 + 72 columns
+    (2, 2, 40, 96, 16, 1, 1, 0, 8, True, True),       # 2 waves: one per tile group; 1 x 1 kernel; 96 columns: three tiles of a quad
+    (1, 2, 32, 160, 32, 3, 3, 1, 4, True, False),     # F = 4: one slot per thread and pass
+    (3, 3, 64, 138, 64, 3, 3, 0, 16, False, False),   # VALID: W_out = 136, H_out = 62: the last slots of the last folded column are dropped
 ]
 
 
