@@ -506,12 +506,11 @@ def main():
                 nchw[axis_name].update({"fused_total_ms": fz_ms, "fused_forward_ms": fk_ms,
                                         "fused_forward_GBps": (sn.x_bytes + sn.y_bytes) / (fk_ms * 1e-3) / 1e9,
                                         "fused_useful_tflops": sn.useful_flops / (fz_ms * 1e-3) / 1e12})
-                if axis == fc.FOLD_H:
-                    # ... and reads x channels-first itself: one launch, no folded copy of the input either
-                    _, fi_ms = time_events(lambda: fc.foldconv_forward(pn, xn, w_exp_n, bn, yn, ws_n,
-                                                                       fc.FLAG_IN_NCHW | fc.FLAG_OUT_NCHW | fc.FLAG_FILTER_PACKED), 20, 5)
-                    nchw[axis_name].update({"one_launch_ms": fi_ms,
-                                            "one_launch_useful_tflops": sn.useful_flops / (fi_ms * 1e-3) / 1e12})
+                # ... and reads x channels-first itself: one launch, no folded copy of the input either
+                _, fi_ms = time_events(lambda: fc.foldconv_forward(pn, xn, w_exp_n, bn, yn, ws_n,
+                                                                   fc.FLAG_IN_NCHW | fc.FLAG_OUT_NCHW | fc.FLAG_FILTER_PACKED), 20, 5)
+                nchw[axis_name].update({"one_launch_ms": fi_ms,
+                                        "one_launch_useful_tflops": sn.useful_flops / (fi_ms * 1e-3) / 1e12})
             del w_exp_n, ws_n, xf_n, yn
         extras["nchw"] = nchw
     if "fold_choice" in want:

@@ -95,11 +95,13 @@ enum {
                                          read): the launch applies the fold in its load
                                          addressing and no folded copy is made.  Only together
                                          with FOLDCONV_FLAG_OUT_NCHW (FOLDCONV_ERR_BADARG
-                                         without) and for height-folded plans whose
-                                         shapes.out_nchw_fused is 1 (else
-                                         FOLDCONV_ERR_UNSUPPORTED: with a width fold the lanes of
-                                         such a read lie F elements apart, and the separate fold
-                                         pass is faster); same bits as the two-step route         */
+                                         without), where shapes.out_nchw_fused is 1; a width fold
+                                         must also fit the input rows of a tile in LDS beside
+                                         its output tiles (W a multiple of 8, H_out * W'_out a
+                                         multiple of 32, W_out <= W, at most F*C_out 16-byte pieces
+                                         in those rows); else FOLDCONV_ERR_UNSUPPORTED and the
+                                         caller runs foldconv_fold_input_nchw first.  Same bits
+                                         as the two-step route                                     */
 };
 
 /* Which image axis of a channels-first (NCHW) tensor is folded into the channels. */
@@ -303,9 +305,9 @@ FOLDCONV_API int foldconv_pack_filter_compact(foldconv_plan_t plan, const void *
  * With FOLDCONV_FLAG_OUT_NCHW the reconstructed output is written
  * channels-first, y[n][co][h][F*w'+g] for a width fold and
  * y[n][co][F*h'+g][w] for a height fold (shapes.y_bytes, 16-byte aligned);
- * with FOLDCONV_FLAG_IN_NCHW as well (height folds), x_fold is the
- * channels-first input x[n][c][h][w] (paper: Eq. "width_fold_def" along h,
- * x'[n][w][h'][f*C+c] = x[n][c][F*h'+f][w], applied on the fly).
+ * with FOLDCONV_FLAG_IN_NCHW as well, x_fold is the channels-first input
+ * x[n][c][h][w] (paper: Eq. "width_fold_def", x'[n][h][w'][f*C+c] =
+ * x[n][c][h][F*w'+f], resp. the same along h, applied on the fly).
  */
 FOLDCONV_API int foldconv_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp,
                      const void *bias, void *y, void *workspace, size_t workspace_bytes,

@@ -120,13 +120,15 @@ int fc_forward(foldconv_plan_t plan, const void *x_fold, const void *w_exp, cons
     const bool out_nchw = (flags & FOLDCONV_FLAG_OUT_NCHW) != 0;
     const bool in_nchw = (flags & FOLDCONV_FLAG_IN_NCHW) != 0;
     if (in_nchw && !out_nchw) return FOLDCONV_ERR_BADARG;  // only the channels-first kernel gathers its input
-    if (in_nchw && plan->fold_axis != FOLDCONV_FOLD_H) return FOLDCONV_ERR_UNSUPPORTED;  // ... and only along h
+    // (checked below, once the geometry of this call is known: a width fold must fit its stage of input rows in LDS)
     const bool hfold = plan->fold_axis == FOLDCONV_FOLD_H;
     if (out_nchw) {
         if (flags & FOLDCONV_FLAG_KEEP_FOLDED) return FOLDCONV_ERR_BADARG;
         g.out_row = s.W_out;
         int ks = 0;
         if (!s.out_nchw_fused || !fc_stream_nchw_ok(g, g.band, hfold, &ks)) return FOLDCONV_ERR_UNSUPPORTED;
+        NchwStage stage;
+        if (in_nchw && !hfold && !fc_stream_nchw_stage(g, &stage)) return FOLDCONV_ERR_UNSUPPORTED;
     }
     if (compact) {
         // every kernel takes its filter operand from the workspace

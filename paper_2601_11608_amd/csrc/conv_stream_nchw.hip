@@ -40,7 +40,12 @@
 // load read 64 consecutive bytes of one image row; the separate fold pass and its round trip through memory
 // fall away (paper: Eq. "width_fold_def", along h, applied in the load addressing).  For a width fold the
 // same gather would have the lanes F elements apart (x[n][c][a][F*b'+f], b' across the lanes): measured
-// three times slower than the fold pass it replaces, so those plans keep the pass.
+// three times slower than the fold pass it replaces.  Width folds therefore stage the channels-first rows
+// through LDS instead (XW instances): per tile every thread fetches one 16-byte piece of a channel row (eight
+// consecutive image columns of the few input rows the tile's pixels need) and scatters it, 2 bytes at a time,
+// to where those values sit in the folded rows x'[n][h][w*C + c]; the waves then read their fragments from that
+// copy with 16-byte LDS reads.  Two such stage buffers alternate, so the trip keeps its single barrier; the
+// piece of the tile after next stays in flight across the write-out like the fragments it replaces.
 // paper: Eq. "new_conv_H", Eq. "bias_construct"; the Reconstruct step
 // w = F w' + f (h = F h' + f for a height fold), applied on the way to a channels-first tensor.
 #include <hip/hip_runtime.h>
@@ -83,9 +88,12 @@ struct NchwArgs {
     int skew;             // extra bytes in front of every further group of 8 slots (LDS bank spread)
     unsigned tiles_ab;    // HF: tile pairs per folded column, ceil(Hout / 64)
     unsigned pace;        // wall-clock ticks * 256 between a workgroup's store bursts, 0 = unpaced (fc_store_pace)
-    // XN: element strides of the channels-first input: one channel plane, one step along the plan's rows,
+    // XN, XW: element strides of the channels-first input: one channel plane, one step along the plan's rows,
     // one step along the plan's (unfolded) columns
     unsigned xP, xsA, xsB;
+    // XW: the stage of folded input rows in LDS: rows per buffer, bytes per row (zero halo, the row, zero halo),
+    // elements of the halo in front, 16-byte pieces per channel row of the image
+    int stage_rows, stage_pitch, halo_l, xW8;
 };
 
 template <int I, int N, class F>
@@ -102,7 +110,7 @@ __device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigne
 }
 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
-template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN, bool HQ>
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN, bool HQ, bool XW>
 __global__ void __launch_bounds__(1024, 1)
 conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                         const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
@@ -110,6 +118,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     using Vec = typename TR::Vec;
     constexpr int NT = 2, COLS = 64;
     static_assert(HF || !HQ, "quads are a height-fold layout");
+    static_assert(!XW || (!HF && !XN), "the staged input read is the width fold's");
     extern __shared__ __attribute__((aligned(16))) unsigned char tile_lds[];  // two (HQ: four) tiles of 32 * pitch bytes
 
     const int t = threadIdx.x;
@@ -327,7 +336,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
     // Nothing the compiler tracks may be in flight when the hand-counted loads start.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    load_tile();
+    if constexpr (!XW) load_tile();
     // Drain the first tile's loads here: the loop head then only ever waits for loads that were
     // issued ahead of the stores of the previous tile, and leaves those stores in flight.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -370,7 +379,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
         for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(bf[nt], ones, zero);
-        if (!EXACT) {
+        if (!EXACT && !XW) {
             // Instances with run-time K guards drain every fragment load here, ahead of the guards:
             // a fragment whose K-step is guarded off is never waited for below, and its registers
             // must not be handed to anything else while its load is still in flight.
@@ -386,7 +395,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 // STORES_BEHIND stores, so the fragment has landed once at most that many operations
                 // are outstanding.  Instances with run-time K guards have drained everything above.
                 constexpr int kBehind = EXACT ? (KHM * KSM - 1 - idx) * LPF + STORES_BEHIND : 0;
-                wait_frag(xf[kh][ks], std::integral_constant<int, kBehind>{});
+                if constexpr (!XW) wait_frag(xf[kh][ks], std::integral_constant<int, kBehind>{});  // XW: read from LDS
                 const Vec xv = frag_vec(xf[kh][ks]);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[nt] = TR::mfma(wf[kh][ks][nt], xv, acc[nt]);
@@ -463,6 +472,111 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
                 write_out(tile_lds + rd_off + half * (slot_step * g.Co * 2), off0, ok);
             }
         }
+    } else if constexpr (XW) {
+        // ---- width fold, channels-first input staged through LDS ----------------------------------------
+        // No tile crosses an image here (the host checks that an image is a whole number of tiles), so a
+        // tile's pixels lie in output rows ho0 .. ho0 + R - 1 of one image and need the input rows
+        // ho0 - pad_h + s, s < stage_rows: stage row s.  Pixel (ho0 + q, wo) reads its fragment for kh from
+        // stage row q + kh at folded column wo*F*C + e; the zero halos at both ends of a stage row and the
+        // zeros that out-of-range loads return are the zero padding.
+        unsigned char *const stage0 = tile_lds + 2 * 32 * a.pitch;
+        const int stage_bytes = a.stage_rows * a.stage_pitch;
+        for (int o = t * 16; o < 2 * stage_bytes; o += (int)blockDim.x * 16)
+            *reinterpret_cast<u32x4 *>(stage0 + o) = u32x4{0u, 0u, 0u, 0u};  // the halos stay zero from here on
+        // this thread's piece of a stage buffer: stage row ps, channel pc, image columns [8*pw8, 8*pw8 + 8)
+        const int per_row = g.C * a.xW8;
+        const int ps = t / per_row, pc = (t - ps * per_row) / a.xW8, pw8 = t - ps * per_row - pc * a.xW8;
+        const bool p_has = ps < a.stage_rows;
+        const int p_lds = ps * a.stage_pitch + (a.halo_l + 8 * pw8 * g.C + pc) * 2;  // + i * C * 2 for column 8*pw8 + i
+        const int p_x = pc * (int)a.xP + 8 * pw8;                                    // + image and row
+        struct Pos { unsigned m0, wo0, ho0, img0; };
+        auto next_pos = [&](Pos &p) {
+            p.m0 += a.deal.stride * 32u;
+            p.wo0 += a.dW;
+            unsigned c = p.wo0 >= (unsigned)g.Wf_out ? 1u : 0u;
+            p.wo0 -= c * (unsigned)g.Wf_out;
+            p.ho0 += a.dH + c;
+            c = p.ho0 >= (unsigned)g.Hout ? 1u : 0u;
+            p.ho0 -= c * (unsigned)g.Hout;
+            p.img0 += a.dI + c;
+        };
+        u32x4 piece;
+        auto piece_load = [&](const Pos &p) {
+            const int hi = (int)p.ho0 - g.pad_h + ps;
+            const bool ok = p_has && p.m0 < (unsigned)g.M && hi >= 0 && hi < g.H;
+            const unsigned voff =
+                ok ? 2u * (unsigned)((int)(p.img0 * (unsigned)g.C) * (int)a.xP + hi * (int)a.xsA + p_x) : kOutOfRangeN;
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(piece) : "v"(voff), "s"(xr) : "memory");
+        };
+        auto piece_store = [&](unsigned char *stage) {
+            if (p_has) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    *reinterpret_cast<unsigned short *>(stage + p_lds + i * g.C * 2) = (unsigned short)(piece[i >> 1] >> (16 * (i & 1)));
+            }
+        };
+        auto read_frags = [&](const unsigned char *stage, const Pos &p) {
+            const unsigned tt = p.wo0 + (unsigned)r;
+            const unsigned q = small_div_n(tt, a.mgW, (unsigned)g.Wf_out);
+            const unsigned wo = tt - q * (unsigned)g.Wf_out;
+            const int at = (int)q * a.stage_pitch + (a.halo_l + (int)wo * g.FC + e0) * 2;
+#pragma unroll
+            for (int kh = 0; kh < KHM; ++kh)
+#pragma unroll
+                for (int ks = 0; ks < KSM; ++ks) {
+                    // K-steps outside the wave's band window multiply zero filter fragments: give them zeros as the
+                    // global path does, whatever the input holds there
+                    // (such a lane reads offset 0: the address it would form may lie past the stage)
+                    const bool use = kh < KH && ((ksmask >> ks) & 1u);
+                    const u32x4 v = *reinterpret_cast<const u32x4 *>(stage + (use ? at + kh * a.stage_pitch + 32 * ks : 0));
+                    xf[kh][ks] = use ? v : u32x4{0u, 0u, 0u, 0u};
+                }
+        };
+        Pos A = {m0, wo0, ho0, img0}, B = A;
+        next_pos(B);
+        Pos C = B;
+        next_pos(C);
+        __syncthreads();  // the stage buffers are zero
+        piece_load(A);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(piece) : : "memory");
+        piece_store(stage0);
+        piece_load(B);
+        // Four stores that the range check drops, so that from the first trip on exactly four stores lie behind the
+        // piece in flight when the loop waits for it.
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{0u, 0u, 0u, 0u}, yr, kOutOfRangeN, 0, 2 /* nt */);
+        __syncthreads();
+        read_frags(stage0, A);
+        int buf = 0;
+        for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
+            floatx16_t acc[NT];
+            multiply(acc, std::integral_constant<int, 4>{});
+            // the next tile's piece has landed: behind its load lie the four stores of the tile before this one
+            asm volatile("s_waitcnt vmcnt(4)" : "+v"(piece) : : "memory");
+            unsigned char *const stage_next = stage0 + (buf ^ 1) * stage_bytes;
+            piece_store(stage_next);
+            unsigned char *tb = tile_lds + buf * (32 * a.pitch);
+            assemble(acc, tb);
+            // One barrier per tile: behind it the tile is assembled and the next tile's rows are staged.  Either
+            // buffer is written again two tiles on, after the barrier of the tile between, which every wave passes
+            // only after its reads of that buffer.
+            __syncthreads();
+            piece_load(C);  // the tile after next; past the end every lane's offset is out of range
+            pace();
+            // ---- write out y[img][4*co4+i][ho][F*wo + 8*sg8 .. +8) for i = 0..3 ----
+            unsigned wo, ho, img;
+            pixel(A.wo0, A.ho0, A.img0, (unsigned)sp, wo, ho, img);
+            const bool ok = A.m0 + (unsigned)sp < (unsigned)g.M;
+            const unsigned off0 = 2u * (((img * (unsigned)g.Co + 4u * (unsigned)co4) * (unsigned)g.Hout + ho) * (unsigned)g.out_row +
+                                        wo * (unsigned)g.F + 8u * (unsigned)sg8);
+            write_out(tb + rd_off, off0, ok);
+            read_frags(stage_next, B);
+            A = B;
+            B = C;
+            next_pos(C);
+            buf ^= 1;
+        }
     } else {
         int buf = 0;
         for (unsigned mt = t_first; mt < a.MT; mt += a.deal.stride) {
@@ -495,11 +609,21 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
 static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
 
-template <typename TR, int KHM, int KSM, bool HF, bool XN, bool HQ>
+template <typename TR, int KHM, int KSM, bool HF, bool XN, bool HQ, bool XW>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
     NchwArgs a;
-    if (HF) {
+    NchwStage stage = {0, 0, 0, 0};
+    if (XW && !fc_stream_nchw_stage(g, &stage)) return (int)hipErrorInvalidValue;
+    a.stage_rows = stage.rows;
+    a.stage_pitch = stage.pitch;
+    a.halo_l = stage.halo_l;
+    a.xW8 = g.Wf * g.F / 8;
+    if (XW) {
+        // no skew here: the stage buffers need its 16 KB (fc_stream_nchw_stage sized them for this pitch)
+        a.skew = 0;
+        a.pitch = g.NCo * 2 + 8;
+    } else if (HF) {
         // a thread of the write-out reads pixels 8 rows apart and eight neighbouring lanes read pixels 8k .. 8k+7
         // of the pair: with a pitch of 8 bytes (mod 32) the lanes of a wave spread over all banks in both phases
         a.skew = 0;
@@ -510,7 +634,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
         if (a.skew % 8 != 0) a.skew = 8;
         a.pitch = g.NCo * 2 + g8n * a.skew + 8;
     }
-    const unsigned lds_bytes = (HQ ? 4u : 2u) * 32u * (unsigned)a.pitch;
+    const unsigned lds_bytes = (HQ ? 4u : 2u) * 32u * (unsigned)a.pitch + 2u * (unsigned)(stage.rows * stage.pitch);
     const unsigned threads = (unsigned)g.NCo;  // one wave per 64 columns
     // workgroups resident per compute unit: 16 waves at the register budget of the launch bounds, 160 KB of LDS
     unsigned per_cu = 1024u / threads;
@@ -551,8 +675,8 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \
     do {                                                                                                     \
-        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ>>()) return e; \
-        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ><<<blocks, threads, lds_bytes, st>>>(       \
+        if (int e = fc_allow_full_lds<conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ, XW>>()) return e; \
+        conv_stream_nchw_kernel<TR, KHM, KSM, EX, RL, HF, XN, HQ, XW><<<blocks, threads, lds_bytes, st>>>(       \
             g, a, (const T *)x, (const u32x4 *)wp, (const T *)bias, (T *)y);                                 \
     } while (0)
     if (exact && g.relu) FC_GO(true, true);
@@ -563,10 +687,10 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     return (int)hipGetLastError();
 }
 
-template <typename TR, bool HF, bool XN, bool HQ>
+template <typename TR, bool HF, bool XN, bool HQ, bool XW = false>
 int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
-    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN, HQ>(g, ksteps, x, wp, bias, y, st);
-    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN, HQ>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN, HQ, XW>(g, ksteps, x, wp, bias, y, st);
+    if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN, HQ, XW>(g, ksteps, x, wp, bias, y, st);
     return (int)hipErrorInvalidValue;
 }
 
@@ -582,7 +706,7 @@ int launch_layout(const ConvGeom &g, int ksteps, bool height_fold, bool x_nchw, 
         return x_nchw ? launch_any<TR, true, true, false>(g, ksteps, x, wp, bias, y, st)
                       : launch_any<TR, true, false, false>(g, ksteps, x, wp, bias, y, st);
     }
-    if (x_nchw) return (int)hipErrorInvalidValue;  // width folds keep their fold pass (see the head of this file)
+    if (x_nchw) return launch_any<TR, false, false, false, true>(g, ksteps, x, wp, bias, y, st);  // staged through LDS
     return launch_any<TR, false, false, false>(g, ksteps, x, wp, bias, y, st);
 }
 

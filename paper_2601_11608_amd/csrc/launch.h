@@ -76,7 +76,14 @@ int fc_launch_conv_tiled(foldconv_dtype_t dt, const ConvGeom &g, const void *x, 
 // W_out for a width fold, its H_out for a height fold, whose plan is that of the transposed image); false
 // if the geometry does not fit it.
 bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *ksteps);
-// x_nchw: x is the channels-first input itself (same bytes as x' otherwise), gathered element by element.
+// Width folds that read a channels-first input stage its rows through LDS behind the two output tiles: rows per
+// stage buffer, bytes per row (zero halo, the folded row, zero halo) and elements of the halo in front; false where
+// that does not fit (an image must be a whole number of 32-pixel tiles, one 16-byte piece per thread and tile, 160 KB
+// of LDS in all).
+struct NchwStage { int rows, pitch, halo_l; long long lds_bytes; };
+bool fc_stream_nchw_stage(const ConvGeom &g, NchwStage *out);
+// x_nchw: x is the channels-first input itself (same bytes as x' otherwise): gathered element by element (height
+// fold) or staged through LDS (width fold, where fc_stream_nchw_stage allows).
 int fc_launch_conv_stream_nchw(foldconv_dtype_t dt, const ConvGeom &g, bool height_fold, bool x_nchw, const void *x,
                                const void *w_pack, const void *bias, void *y, void *stream);
 // Streaming kernel with the input tile staged through LDS (dense walks whose K extent fits the registers).

@@ -135,6 +135,25 @@ bool fc_stream_nchw_ok(const ConvGeom &g, int band, bool height_fold, int *kstep
     return true;
 }
 
+bool fc_stream_nchw_stage(const ConvGeom &g, NchwStage *out) {
+    const long long W = (long long)g.Wf * g.F;
+    // 16-byte pieces of 8 image columns; no tile crosses an image; the folded output is no wider than the input
+    if (g.eb != 2 || W % 8 != 0 || ((long long)g.Hout * g.Wf_out) % 32 != 0 || g.Wf_out > g.Wf) return false;
+    if (g.e_min > 0 || g.e_max < g.FC) return false;
+    // output rows a tile of 32 consecutive folded pixels can touch, and the input rows under them
+    const int rows = (g.Wf_out - 1 + 31) / g.Wf_out + 1 + g.KH - 1;
+    const long long halo_l = -(long long)g.e_min, halo_r = (long long)g.e_max - g.FC;
+    const long long pitch = ((halo_l + g.in_row + halo_r) * 2 + 15) / 16 * 16;
+    if (halo_l % 8 != 0 || (long long)rows * g.C * (W / 8) > g.NCo) return false;  // one piece per thread and tile
+    const long long lds = 2LL * 32 * (g.NCo * 2 + 8) + 2LL * rows * pitch;
+    if (lds > 163840) return false;
+    out->rows = rows;
+    out->pitch = (int)pitch;
+    out->halo_l = (int)halo_l;
+    out->lds_bytes = lds;
+    return true;
+}
+
 int fc_choose_kernel(const ConvGeom &g, foldconv_dtype_t dt) {
     // Channel counts that miss the chunk alignment, and fp32 or 8-byte-chunk layers too large for the
     // streaming kernel's registers, run the element-gather MFMA kernel (the analogue of

@@ -96,6 +96,7 @@ class ChannelsFirstLayer:
                                           layer.pad, layer.F, fold_axis, w_oihw.dtype)
         s = self.plan.shapes
         self.fused = bool(s.out_nchw_fused)
+        self.one_launch = self.fused  # until a call says the geometry does not allow reading x channels-first
         self.w = w_oihw.to(device).contiguous()
         self.b = None if b is None else b.to(device).contiguous()
         self.w_exp = torch.empty(s.w_exp_bytes // s.elem_bytes, dtype=self.dtype, device=device)
@@ -116,10 +117,15 @@ class ChannelsFirstLayer:
 
     def forward(self, x, y):
         flags = fc.FLAG_FILTER_PACKED | (fc.FLAG_RELU if self.layer.relu else 0)
-        if self.fused and self.plan.shapes.fold_axis == fc.FOLD_H:
+        if self.fused and self.one_launch:
             # one launch: the kernel reads x and writes y channels-first
-            fc.foldconv_forward(self.plan, x, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW | fc.FLAG_IN_NCHW)
-            return y
+            try:
+                fc.foldconv_forward(self.plan, x, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW | fc.FLAG_IN_NCHW)
+                return y
+            except fc.FoldconvError as e:
+                if e.status != -3:  # unsupported: a width fold whose input rows do not fit LDS; fold first from now on
+                    raise
+                self.one_launch = False
         fc.foldconv_fold_input_nchw(self.plan, x, self.x_fold)
         if self.fused:
             fc.foldconv_forward(self.plan, self.x_fold, self.w_exp, self.b, y, self.ws, flags | fc.FLAG_OUT_NCHW)

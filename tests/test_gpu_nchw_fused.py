@@ -46,6 +46,17 @@ def two_step(fc, plan, xf, w_exp, b, ws, flags):
     return y
 
 
+def stage_fits(s):
+    """Width fold: the rows of the channels-first input that a tile needs fit LDS beside the two output tiles
+    (the library's rule, restated: 16-byte pieces, no tile across images, one piece per thread and tile)."""
+    if s.W % 8 or (s.H_out * s.W_out_fold) % 32 or s.W_out_fold > s.W_fold:
+        return False
+    rows = (s.W_out_fold - 1 + 31) // s.W_out_fold + 1 + s.KH - 1
+    halo = -s.d_min * s.C_fold + (s.d_max + 1) * s.C_fold - s.C_fold
+    pitch = -(-(halo + s.W * s.C_in) * 2 // 16) * 16
+    return rows * s.C_in * (s.W // 8) <= s.Co_fold and 2 * 32 * (s.Co_fold * 2 + 8) + 2 * rows * pitch <= 163840
+
+
 def fused(fc, plan, xf, w_exp, b, ws, flags):
     s = plan.shapes
     y = torch.full((s.y_bytes // s.elem_bytes,), float("nan"), dtype=xf.dtype, device="cuda")
@@ -66,6 +77,8 @@ FUSED = [
     (70, 1, 1, 16, 8, 1, 1, 0, 16, True, False),      # one folded pixel per image: a tile spans 32 images
     (5, 1, 3, 32, 16, 3, 3, 1, 16, True, True),       # two folded pixels per row, three rows
     (1, 1, 300, 8, 64, 3, 1, 1, 8, False, False),     # one folded pixel per row, 3 x 1 kernel
+    (2, 2, 11, 64, 24, 2, 3, 1, 8, False, True),      # KH = 2 (guarded instance) on a shape whose channels-first rows fit LDS
+    (2, 2, 8, 64, 16, 1, 1, 0, 8, True, False),       # 1 x 1 kernel, the same; 2 waves
 ]
 
 
@@ -116,9 +129,10 @@ def test_fused_nchw_output(fc, oracle, case, dt):
     got_c = fused(fc, plan, xf, None, b, cws, flags | fc.FLAG_FILTER_COMPACT)
     torch.cuda.synchronize()
     assert torch.equal(got_c.view(torch.int16), want.view(torch.int16))
-    # height folds: the channels-first input read in the same launch (no folded copy): the same bytes again
+    # the channels-first input read in the same launch (no folded copy): the same bytes again.  Height folds
+    # gather it element by element; width folds stage its rows through LDS where those fit
     xn = x.cuda().reshape(-1)
-    if axis == fc.FOLD_H:
+    if axis == fc.FOLD_H or stage_fits(s):
         got_in = fused(fc, plan, xn, w_exp, b, ws, flags | fc.FLAG_IN_NCHW)
         got_in_c = fused(fc, plan, xn, None, b, cws, flags | fc.FLAG_IN_NCHW | fc.FLAG_FILTER_COMPACT)
         torch.cuda.synchronize()
@@ -155,10 +169,9 @@ def test_fused_nchw_headline_layer_full_size(fc, oracle, axis):
     got = fused(fc, plan, xf, w_exp, b, ws, 0)
     torch.cuda.synchronize()
     assert torch.equal(got.view(torch.int16), want.view(torch.int16))
-    if axis == "H":
-        got_in = fused(fc, plan, xn.cuda().reshape(-1), w_exp, b, ws, fc.FLAG_IN_NCHW)      # channels-first on both sides
-        torch.cuda.synchronize()
-        assert torch.equal(got_in.view(torch.int16), want.view(torch.int16))
+    got_in = fused(fc, plan, xn.cuda().reshape(-1), w_exp, b, ws, fc.FLAG_IN_NCHW)      # channels-first on both sides
+    torch.cuda.synchronize()
+    assert torch.equal(got_in.view(torch.int16), want.view(torch.int16))
     y = got.cpu().reshape(l.N, l.C_out, l.H, l.W)
     images = [0, 29, 63]
     ref = oracle.conv_direct_nchw(f64(xn[images]), f64(wn), f64(bs[0]), 1, 1)
