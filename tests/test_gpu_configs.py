@@ -134,6 +134,11 @@ def test_store_pacing_changes_nothing(env):
     for _ in range(4):
         C.forward(xc, y1)
     flags = fc.FLAG_FILTER_PACKED | fc.FLAG_OUT_NCHW | fc.FLAG_UNPACED
+    assert C.one_launch                           # the layer reads x channels-first in the same launch
+    fc.foldconv_forward(C.plan, xc, C.w_exp, C.b, y2, C.ws, flags | fc.FLAG_IN_NCHW)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    fc.foldconv_fold_input_nchw(C.plan, xc, C.x_fold)     # ... and writes what the two-launch route writes
     fc.foldconv_forward(C.plan, C.x_fold, C.w_exp, C.b, y2, C.ws, flags)
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)
