@@ -327,9 +327,10 @@ nchw_to_fold_tile_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ 
 }
 
 // Output: y'[n][a][b][co] (row pitch in b given, columns b >= B cropped: the ragged
-// reconstruct) -> y[n][co][himg][wimg].  A workgroup moves a tile of 64 image columns x 64
+// reconstruct) -> y[n][co][himg][wimg].  A workgroup moves a tile of 128 image columns x 64
 // channels of one image row through LDS: 16-byte loads along co, eight 2-byte LDS reads per
-// lane gather eight consecutive image columns of one channel, one 16-byte store along w.
+// lane gather eight consecutive image columns of one channel, one 16-byte store along w
+// (sixteen lanes write 256 consecutive bytes of a channel row: runs of 128 bytes cost a fifth more).
 struct FoldToNchw {
     int Co, Hi, Wi;             // channels, image rows and columns of y
     long long sN, sH, sW;       // element strides of (n, himg, wimg) in y'
@@ -337,7 +338,7 @@ struct FoldToNchw {
     long long rows;             // N * Hi
 };
 
-constexpr int kTW = 64, kTC = 64;
+constexpr int kTW = 128, kTC = 64;
 constexpr int kTPitch = kTC * 2 + 4;  // bytes per LDS row; 33 dwords: the column gather hits distinct banks
 
 __global__ void __launch_bounds__(kThreads)
@@ -353,7 +354,7 @@ fold_to_nchw_tile_kernel(const uint16_t *__restrict__ yf, uint16_t *__restrict__
         const long long n = row / m.Hi;
         const int hi = (int)(row - n * m.Hi);
         const uint16_t *src = yf + n * m.sN + hi * m.sH;
-        // load: 64 pixels x 8 chunks of 8 channels
+        // load: 128 pixels x 8 chunks of 8 channels
 #pragma unroll
         for (int i = 0; i < (kTW * kTC / 8) / kThreads; ++i) {
             const int q = t + kThreads * i;
@@ -365,11 +366,11 @@ fold_to_nchw_tile_kernel(const uint16_t *__restrict__ yf, uint16_t *__restrict__
             dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
         }
         __syncthreads();
-        // store: per channel, 8 chunks of 8 consecutive image columns
+        // store: per channel, 16 chunks of 8 consecutive image columns
 #pragma unroll
         for (int i = 0; i < (kTW * kTC / 8) / kThreads; ++i) {
             const int q = t + kThreads * i;
-            const int wc = q & 7, c = q >> 3;
+            const int wc = q % (kTW / 8), c = q / (kTW / 8);
             const int wbase = w0 + 8 * wc;
             if (c0 + c < m.Co && wbase < m.Wi) {
                 uint16_t v[8];
