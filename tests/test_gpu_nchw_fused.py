@@ -149,6 +149,60 @@ def test_fused_nchw_output(fc, oracle, case, dt):
         assert rel_l2_per_image(f64(got.cpu()).reshape(ref.shape), ref) <= TOL[dt]
 
 
+@pytest.mark.parametrize("chunk", range(4))
+def test_fused_nchw_random_geometries(fc, chunk):
+    """Seeded random shapes that the channels-first kernel serves, both folds: the one-launch call (channels-first
+    input and output) and the fused-output call write the bytes of the two-step route (which the other tests tie to
+    the oracle).  Shapes are drawn so that pairs and quads of tiles, the staged and the gathered input read, ragged
+    tiles and images that are not a whole number of tiles all occur."""
+    rng = np.random.RandomState(4100 + chunk)
+    ran, one_launch, two_launch = 0, 0, 0
+    tries = 0
+    while ran < 12 and tries < 400:
+        tries += 1
+        axis = fc.FOLD_H if rng.rand() < 0.5 else fc.FOLD_W
+        N, C = int(rng.randint(1, 4)), int(rng.choice([1, 2, 3, 4]))
+        Co = int(rng.choice([8, 16, 32, 64]))
+        F = int(rng.choice([4, 8, 16] if axis == fc.FOLD_H else [8, 16, 32]))
+        k = int(rng.choice([1, 3]))
+        KH, KW, pad = k, k, k // 2
+        # the folded axis is a multiple of F, the other one a multiple of 8
+        a_fold = F * int(rng.randint(1, 9))
+        a_other = 8 * int(rng.randint(1, 26))
+        H, W = (a_fold, a_other) if axis == fc.FOLD_H else (a_other, a_fold)
+        if F * Co > 1024 or (F * Co) % 64:
+            continue
+        plan = fc.foldconv_plan_nchw(N, C, H, W, Co, KH, KW, pad, F, axis, torch.float16)
+        s = plan.shapes
+        if not s.out_nchw_fused:
+            continue
+        dt = "f16" if rng.rand() < 0.5 else "bf16"
+        if dt == "bf16":
+            plan = fc.foldconv_plan_nchw(N, C, H, W, Co, KH, KW, pad, F, axis, torch.bfloat16)
+            s = plan.shapes
+        seed = int(rng.randint(1 << 30))
+        x = draw((N, C, H, W), dt, seed)
+        w = (draw((Co, C, KH, KW), dt, seed + 1) * (1.0 / np.sqrt(KH * KW * C))).to(TORCH_DT[dt])
+        b = draw((Co,), dt, seed + 2).cuda() if rng.rand() < 0.7 else None
+        flags = fc.FLAG_RELU if rng.rand() < 0.5 else 0
+        print("random fused nchw", "H" if axis == fc.FOLD_H else "W", (N, C, H, W, Co, KH, KW, pad, F), dt, flush=True)
+        xf, w_exp, ws = prepare(fc, plan, x, w)
+        want = two_step(fc, plan, xf, w_exp, b, ws, flags)
+        got = fused(fc, plan, xf, w_exp, b, ws, flags)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+        try:
+            got_in = fused(fc, plan, x.cuda().reshape(-1), w_exp, b, ws, flags | fc.FLAG_IN_NCHW)
+            torch.cuda.synchronize()
+            assert torch.equal(got_in.view(torch.int16), want.view(torch.int16))
+            one_launch += 1
+        except fc.FoldconvError as e:
+            assert e.status == -3 and axis == fc.FOLD_W and not stage_fits(s)
+            two_launch += 1
+        ran += 1
+    assert ran == 12 and one_launch >= 6
+
+
 @pytest.mark.parametrize("axis", ["W", "H"])
 def test_fused_nchw_headline_layer_full_size(fc, oracle, axis):
     """The headline layer (N=64, 3x224x224 -> 64 channels, fp16, F=16) written channels-first in one
