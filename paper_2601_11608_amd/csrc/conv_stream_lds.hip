@@ -65,7 +65,6 @@ template <typename TR, int KHM, int QM, bool RELU>
 __global__ void __launch_bounds__(256, 1)
 conv_stream_lds_kernel(ConvGeom g, LdsArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                        const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
-    using T = typename TR::T;
     using Vec = typename TR::Vec;
     constexpr int NT = 2, COLS = 64;
     constexpr int KSM = QM / 2;                 // K-steps of 16 per kh
