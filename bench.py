@@ -156,6 +156,10 @@ def fold_choice_table(fc, runner, wl, torch):
     filter, rotating buffers, graph replay), beside the cost model's estimate and its pick."""
     named = [("c2", wl.CONFIGS["c2"][0]), ("c3", wl.CONFIGS["c3"][0]), ("c4", wl.CONFIGS["c4"][0])]
     named += [("c5_L%d" % (i + 1), l) for i, l in enumerate(wl.CONFIGS["c5"])]
+    # the fp32 path: the small fp32 configuration, and the headline shape in fp32
+    c2_f32 = wl.Layer(**{**wl.CONFIGS["c2"][0].__dict__})
+    c2_f32.dtype = "f32"
+    named += [("c1", wl.CONFIGS["c1"][0]), ("c2_f32", c2_f32)]
     table = {}
     for name, base in named:
         pick = fc.foldconv_choose_fold(base.N, base.H, base.W, base.C_in, base.C_out, base.KH, base.KW, base.pad,
