@@ -26,6 +26,7 @@ def fc():
 LAYERS = [
     ("c1", 1, 1, 32, 32, 3, 16, 3, 3, 1, "f32", False, False),
     ("c2", 64, 2, 224, 224, 3, 64, 3, 3, 1, "f16", True, False),
+    ("c2_f32", 64, 2, 224, 224, 3, 64, 3, 3, 1, "f32", True, False),
     ("c3", 32, 2, 112, 112, 12, 48, 3, 3, 1, "bf16", False, False),
     ("c4", 16, 2, 1, 16000, 1, 64, 1, 9, 4, "f16", False, False),
     ("c5_L1", 32, 2, 112, 112, 3, 20, 3, 3, 1, "bf16", False, True),
