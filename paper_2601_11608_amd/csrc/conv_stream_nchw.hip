@@ -26,12 +26,14 @@
 // columns of a channel row: whole 128-byte lines (half lines, written tile by tile, cost a
 // quarter of the launch).
 //
-// HQ instances (height folds whose F*C_out is a multiple of 128) go one step further: a workgroup owns half of
-// the columns (the slots of one half of the fold) for its whole life and assembles *four* tiles, 128 plan rows, in
-// the same LDS before writing them out, its waves forming two groups that compute two of the four tiles each.
-// Sixteen neighbouring lanes then store 256 consecutive bytes of a channel row.  A stand-alone stream of these
-// store patterns over the 411 MB output of the headline layer takes 100 us with 128-byte runs and 83 us with
-// 256-byte runs (68 us with the 1 KB runs of the width fold): the store pattern is what bounds this kernel.
+// HQ instances (height folds whose F*C_out is a multiple of 128 or 256) go further: a workgroup owns one of HQ = 2
+// or 4 parts of the columns (the slots of that part of the fold) for its whole life and assembles 2 * HQ tiles,
+// 128 or 256 plan rows, in the same LDS before writing them out, its waves forming HQ groups that compute two of
+// the tiles each.  Sixteen or thirty-two neighbouring lanes then store 256 consecutive bytes, or a whole row, of a
+// channel plane, and the lanes behind them the rows below it in the same plane.  A stand-alone stream of these
+// store patterns over the 411 MB output of the headline layer takes 100 us with 128-byte runs, 83 us with
+// 256-byte runs or whole rows, 78 us with the rows of one channel next to each other in a wave (68 us with the
+// 1 KB runs of the width fold): the store pattern is what bounds this kernel.
 //
 // XN instances (height folds) read a channels-first input as well: the folded pixel's channel f*C_in + c of
 // plan row a is x[n][c][F*b'+f][a], so a lane's fragment of eight K-contiguous values is gathered with eight
@@ -110,7 +112,8 @@ __device__ __forceinline__ unsigned small_div_n(unsigned t, unsigned mg, unsigne
 }
 
 // EXACT: g.KH == KHM and a.ksteps == KSM, so the K loops carry no run-time guards.
-template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN, bool HQ, bool XW>
+// HQ: 0, or the number of parts the columns are divided into (2 or 4; one workgroup each, 2 * HQ tiles per block of rows)
+template <typename TR, int KHM, int KSM, bool EXACT, bool RELU, bool HF, bool XN, int HQ, bool XW>
 __global__ void __launch_bounds__(1024, 1)
 conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict__ x, const u32x4 *__restrict__ wp,
                         const typename TR::T *__restrict__ bias, typename TR::T *__restrict__ y) {
@@ -128,9 +131,11 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     // Workgroup b runs on XCD b % parts; M tiles follow the workgroups in chunks (FcDeal).  HQ: two workgroups on
     // the same XCD, one per half of the columns, walk the same quads.
     const unsigned xcd = blockIdx.x % a.deal.parts, wg = blockIdx.x / a.deal.parts;
-    const int col_half = HQ ? (int)(wg & 1u) : 0;
-    const int col0 = col_half * (g.NCo >> 1);            // first column the workgroup's LDS tiles hold
-    const int wpg = HQ ? (int)(blockDim.x >> 7) : 1;     // HQ: waves per tile group = (F*C_out / 2) / 64
+    constexpr int QP = HQ ? HQ : 1;
+    static_assert(HQ == 0 || HQ == 2 || HQ == 4, "pairs, or the columns in two or four parts");
+    const int col_half = HQ ? (int)(wg % (unsigned)QP) : 0;
+    const int col0 = col_half * (g.NCo / QP);            // first column the workgroup's LDS tiles hold
+    const int wpg = HQ ? (int)(blockDim.x / (64 * QP)) : 1;  // HQ: waves per tile group = (F*C_out / QP) / 64
     const int tg = HQ ? wave / wpg : 0;                  // HQ: the wave computes tiles 2*tg and 2*tg + 1 of a quad
     const int n_lo = HQ ? col0 + (wave - tg * wpg) * COLS : wave * COLS;
     const int KH = EXACT ? KHM : g.KH, KS = EXACT ? KSM : a.ksteps;
@@ -200,13 +205,15 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     const int g8n = HF ? 1 : g.F >> 3;
     const int per_c4 = 32 * g8n;
     const int c4n = g.Co >> 2;
-    constexpr int DAB = HQ ? 4 : 3;  // log2 of the 8-pixel groups along the plan rows of a pair or quad
-    const int co4 = HF ? (t >> DAB) % c4n : t / per_c4;
+    constexpr int DAB = HQ ? (QP == 2 ? 4 : 5) : 3;  // log2 of the 8-pixel groups along the plan rows of a pair or quad
+    const int slot_step = HQ ? g.F / (2 * QP) : g.F >> 1;   // HF: the thread's second slot lies this far from its first
+    // (HQ: the lanes run over the rows of one channel quadruple before they go on to the next: a wave's store covers
+    // neighbouring rows of one channel plane, 74 us on the headline layer against 85 us with the channels next)
+    const int co4 = HF ? (HQ ? t / ((1 << DAB) * slot_step) : (t >> DAB) % c4n) : t / per_c4;
     const int sp = HF ? 0 : (t - co4 * per_c4) / g8n;
     const int sg8 = HF ? 0 : (t - co4 * per_c4) - sp * g8n;
     const int da8 = HF ? t & ((1 << DAB) - 1) : 0;
-    const int hg = HF ? t / ((1 << DAB) * c4n) : 0;  // below F/2 (HQ: F/4): the block has F*C_out threads
-    const int slot_step = HQ ? g.F >> 2 : g.F >> 1;   // HF: the thread's second slot lies this far from its first
+    const int hg = HF ? (HQ ? (t >> DAB) % slot_step : t / ((1 << DAB) * c4n)) : 0;  // below slot_step: the block has F*C_out threads
     // W fold: + k * C_out * 2 per slot; HF: + k * pitch per pixel, + slot_step * C_out * 2 for the second slot
     const int rd_off = HF ? ((da8 >> 2) * 32 + 8 * (da8 & 3)) * a.pitch + (hg * g.Co + 4 * co4) * 2
                           : sp * a.pitch + (8 * sg8 * g.Co + 4 * co4) * 2 + sg8 * a.skew;
@@ -214,7 +221,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
     // bytes per channel plane: image H_out x W_out (W fold: Hout x out_row; HF: out_row x Hout, the plan is transposed)
     const unsigned plane_b = 2u * (unsigned)g.Hout * (unsigned)g.out_row;
 
-    const unsigned t_first = fc_deal_first_tile(a.deal, xcd, HQ ? wg >> 1 : wg);  // the workgroup's first tile
+    const unsigned t_first = fc_deal_first_tile(a.deal, xcd, HQ ? wg / (unsigned)QP : wg);  // the workgroup's first tile
 
     // The workgroup's current tile.  W fold: 32 consecutive folded pixels from m0 = (img0, ho0, wo0), advanced
     // incrementally.  HF: tile pair `tile` = (img0 * tiles_ab + pair) * Wf_out + wo0 (folded column fastest:
@@ -233,7 +240,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             const unsigned rb = tl / (unsigned)g.Wf_out;  // (image, pair)
             wo0 = tl - rb * (unsigned)g.Wf_out;
             img0 = rb / a.tiles_ab;
-            row0 = (rb - img0 * a.tiles_ab) * (HQ ? 128u : 64u);
+            row0 = (rb - img0 * a.tiles_ab) * (unsigned)(64 * QP);
             ho0 = row0 + 32u * (HQ ? 2u * (unsigned)tg + sub : sub);
         } else {
             wo0 = m0 % (unsigned)g.Wf_out;
@@ -464,7 +471,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
             const unsigned w0 = cur_ho0 + 8u * (unsigned)da8;  // first image column of the piece
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                const unsigned slot = (unsigned)(col_half * (g.F >> 1) + hg + half * slot_step);
+                const unsigned slot = (unsigned)(col_half * (g.F / QP) + hg + half * slot_step);
                 const unsigned h = cur_wo0 * (unsigned)g.F + slot;  // image row
                 const bool ok = h < (unsigned)g.out_row && w0 < (unsigned)g.Hout;  // Hout % 8 == 0: a piece is whole or absent
                 const unsigned off0 =
@@ -609,7 +616,7 @@ conv_stream_nchw_kernel(ConvGeom g, NchwArgs a, const typename TR::T *__restrict
 
 static unsigned magic_for(unsigned d) { return d <= 1 ? 0u : (unsigned)(((1ULL << 32) + d - 1) / d); }
 
-template <typename TR, int KHM, int KSM, bool HF, bool XN, bool HQ, bool XW>
+template <typename TR, int KHM, int KSM, bool HF, bool XN, int HQ, bool XW>
 int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     using T = typename TR::T;
     NchwArgs a;
@@ -627,26 +634,26 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
         // a thread of the write-out reads pixels 8 rows apart and eight neighbouring lanes read pixels 8k .. 8k+7
         // of the pair: with a pitch of 8 bytes (mod 32) the lanes of a wave spread over all banks in both phases
         a.skew = 0;
-        a.pitch = (HQ ? g.NCo / 2 : g.NCo) * 2 + 8;  // HQ: a workgroup's tiles hold half of the columns
+        a.pitch = (HQ ? g.NCo / HQ : g.NCo) * 2 + 8;  // HQ: a workgroup's tiles hold its part of the columns
     } else {
         const int g8n = g.F / 8;
         a.skew = g8n > 1 ? 256 / g8n : 0;
         if (a.skew % 8 != 0) a.skew = 8;
         a.pitch = g.NCo * 2 + g8n * a.skew + 8;
     }
-    const unsigned lds_bytes = (HQ ? 4u : 2u) * 32u * (unsigned)a.pitch + 2u * (unsigned)(stage.rows * stage.pitch);
+    const unsigned lds_bytes = (HQ ? 2u * HQ : 2u) * 32u * (unsigned)a.pitch + 2u * (unsigned)(stage.rows * stage.pitch);
     const unsigned threads = (unsigned)g.NCo;  // one wave per 64 columns
     // workgroups resident per compute unit: 16 waves at the register budget of the launch bounds, 160 KB of LDS
     unsigned per_cu = 1024u / threads;
     if (per_cu > 163840u / lds_bytes) per_cu = 163840u / lds_bytes;
     if (per_cu < 1) per_cu = 1;
-    a.tiles_ab = HQ ? (unsigned)((g.Hout + 127) / 128) : (unsigned)((g.Hout + 63) / 64);
+    a.tiles_ab = HQ ? (unsigned)((g.Hout + 64 * HQ - 1) / (64 * HQ)) : (unsigned)((g.Hout + 63) / 64);
     a.MT = HF ? (unsigned)((long long)g.N * a.tiles_ab * g.Wf_out) : (unsigned)((g.M + 31) / 32);
     FcDevice dev;
     if (int e = fc_device(&dev)) return e;
     // HF: the Wf_out tiles of a row block share all their input rows; keep them in one chunk (one L2)
     // HQ: two workgroups (the two halves of the columns) walk the same quads: half as many walkers
-    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu / (HQ ? 2u : 1u), g.KH, HF ? 8 * g.Wf_out : g.Wf_out);
+    a.deal = fc_make_deal(a.MT, dev.xcds, dev.cus / dev.xcds * per_cu / (HQ ? (unsigned)HQ : 1u), g.KH, HF ? 8 * g.Wf_out : g.Wf_out);
     const long long S = 32LL * a.deal.stride, plane = (long long)g.Hout * g.Wf_out;
     a.dI = (unsigned)(S / plane);
     a.dH = (unsigned)((S % plane) / g.Wf_out);
@@ -671,7 +678,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     a.pace = g.unpaced ? 0u
                        : fc_store_pace((double)a.x_bytes + (double)a.y_bytes, (a.MT + a.deal.stride - 1) / a.deal.stride,
                                        dev.wall_khz, 6.8e12);
-    const unsigned blocks = a.deal.J * a.deal.parts * (HQ ? 2u : 1u);
+    const unsigned blocks = a.deal.J * a.deal.parts * (HQ ? (unsigned)HQ : 1u);
     const bool exact = g.KH == KHM && ksteps == KSM;
 #define FC_GO(EX, RL)                                                                                        \
     do {                                                                                                     \
@@ -687,7 +694,7 @@ int launch_inst(const ConvGeom &g, int ksteps, const void *x, const void *wp, co
     return (int)hipGetLastError();
 }
 
-template <typename TR, bool HF, bool XN, bool HQ, bool XW = false>
+template <typename TR, bool HF, bool XN, int HQ, bool XW = false>
 int launch_any(const ConvGeom &g, int ksteps, const void *x, const void *wp, const void *bias, void *y, hipStream_t st) {
     if (g.KH <= 1 && ksteps <= 2) return launch_inst<TR, 1, 2, HF, XN, HQ, XW>(g, ksteps, x, wp, bias, y, st);
     if (g.KH <= 3 && ksteps <= 1) return launch_inst<TR, 3, 1, HF, XN, HQ, XW>(g, ksteps, x, wp, bias, y, st);
@@ -700,14 +707,20 @@ int launch_layout(const ConvGeom &g, int ksteps, bool height_fold, bool x_nchw, 
     if (height_fold) {
         // quads of four tiles where the two halves of the fold are whole waves, a thread of the write-out has its
         // two slots and the image is wide enough for 256-byte runs to exist
-        const bool quads = g.NCo % 128 == 0 && g.F % 4 == 0 && g.Hout > 64;
-        if (quads) return x_nchw ? launch_any<TR, true, true, true>(g, ksteps, x, wp, bias, y, st)
-                                 : launch_any<TR, true, false, true>(g, ksteps, x, wp, bias, y, st);
-        return x_nchw ? launch_any<TR, true, true, false>(g, ksteps, x, wp, bias, y, st)
-                      : launch_any<TR, true, false, false>(g, ksteps, x, wp, bias, y, st);
+        // the columns in four parts and blocks of eight tiles (whole rows of images up to 256 columns wide) where a
+        // part is whole waves, a thread of the write-out has its two slots and the image is wide enough to gain;
+        // else in two parts and blocks of four tiles; else pairs
+        const bool p4 = g.NCo % 256 == 0 && g.F % 8 == 0 && g.Hout > 128;
+        const bool p2 = g.NCo % 128 == 0 && g.F % 4 == 0 && g.Hout > 64;
+        if (p4) return x_nchw ? launch_any<TR, true, true, 4>(g, ksteps, x, wp, bias, y, st)
+                              : launch_any<TR, true, false, 4>(g, ksteps, x, wp, bias, y, st);
+        if (p2) return x_nchw ? launch_any<TR, true, true, 2>(g, ksteps, x, wp, bias, y, st)
+                              : launch_any<TR, true, false, 2>(g, ksteps, x, wp, bias, y, st);
+        return x_nchw ? launch_any<TR, true, true, 0>(g, ksteps, x, wp, bias, y, st)
+                      : launch_any<TR, true, false, 0>(g, ksteps, x, wp, bias, y, st);
     }
-    if (x_nchw) return launch_any<TR, false, false, false, true>(g, ksteps, x, wp, bias, y, st);  // staged through LDS
-    return launch_any<TR, false, false, false>(g, ksteps, x, wp, bias, y, st);
+    if (x_nchw) return launch_any<TR, false, false, 0, true>(g, ksteps, x, wp, bias, y, st);  // staged through LDS
+    return launch_any<TR, false, false, 0>(g, ksteps, x, wp, bias, y, st);
 }
 
 }  // namespace

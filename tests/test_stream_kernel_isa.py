@@ -191,15 +191,15 @@ def nchw_asm():
 
 def test_channels_first_kernel_waits(nchw_asm):
     names = sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_123conv_stream_nchw_kernelI\S+?):", nchw_asm, re.M)))
-    # two dtypes x two (KH, K-step) shapes x exact/guarded x ReLU x (width fold; height fold in pairs or quads of tiles; each also with a channels-first input)
-    assert len(names) == 96
+    # two dtypes x two (KH, K-step) shapes x exact/guarded x ReLU x (width fold; height fold in blocks of two, four or eight tiles; each also with a channels-first input)
+    assert len(names) == 128
     for name in names:
-        exact = re.search(r"TraitsLi\d+ELi\d+ELb([01])ELb[01]ELb[01]ELb[01]ELb[01]ELb[01]E", name).group(1) == "1"
+        exact = re.search(r"TraitsLi\d+ELi\d+ELb([01])ELb[01]ELb[01]ELb[01]ELi\d+ELb[01]E", name).group(1) == "1"
         lines = instructions(nchw_asm, name)
         partial = walk_paths(lines, name)
         counts = [int(w) for l in lines for w in re.findall(r"s_waitcnt.*vmcnt\((\d+)\)", l)]
         # the last template argument: width fold with the channels-first input staged through LDS
-        staged = re.search(r"TraitsLi\d+ELi\d+ELb[01]ELb[01]ELb[01]ELb[01]ELb[01]ELb([01])E", name).group(1) == "1"
+        staged = re.search(r"TraitsLi\d+ELi\d+ELb[01]ELb[01]ELb[01]ELb[01]ELi\d+ELb([01])E", name).group(1) == "1"
         if exact or staged:
             # the stores of the previous tile stay in flight: some waits leave 4 or more outstanding
             # (a staged instance waits that way for its piece of the input, guarded K loop or not)
@@ -217,7 +217,7 @@ def test_channels_last_kernel_waits_by_path_walk(asm):
 @pytest.mark.parametrize("mutation", ["weak_wait", "drop_store"])
 def test_path_walk_catches_planted_mistakes(nchw_asm, mutation):
     name = next(n for n in sorted(set(re.findall(r"^(_ZN12_GLOBAL__N_123conv_stream_nchw_kernelI\S+?):", nchw_asm, re.M)))
-                if "Li3ELi1ELb1ELb0ELb0ELb0ELb0ELb0E" in n)
+                if "Li3ELi1ELb1ELb0ELb0ELb0ELi0ELb0E" in n)
     lines = instructions(nchw_asm, name)
     walk_paths(lines, name)
     bad = list(lines)
