@@ -1,5 +1,5 @@
-// Streaming MFMA convolution with a channels-first (NCHW) output, for width-folded
-// plans of small-K layers.
+// Streaming MFMA convolution with a channels-first (NCHW) output (and, on request, input),
+// for width- and height-folded plans of small-K layers.
 //
 // The filter-stationary streaming kernel gives every wave 64 output columns
 // n = g*C_out + co, i.e. (part of) one output slot g.  In a channels-first
